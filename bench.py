@@ -1,0 +1,187 @@
+"""Benchmark of the BUZZ decode hot path on one MI355X.
+
+One "step" = one decode step of every layer: append, split decode attention over the retained cache,
+score accumulation, and the beehive eviction whenever T tokens have been buffered.  Inputs are seeded,
+synthetic and resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="llama7b_layer")
+    ap.add_argument("--layers", type=int, default=None, help="override the workload's layer count")
+    ap.add_argument("--splits", type=int, default=0, help="key-range splits per unit (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
+                    help="rocprofv3 FETCH_SIZE / WRITE_SIZE per attention launch (scaled KiB) to report as traffic")
+    return ap.parse_args()
+
+
+def make_caches(wl, layers, max_context, splits, flags):
+    from paper_2410_23079_amd import BuzzCache, BuzzConfig
+    caches = []
+    for _ in range(layers):
+        c = BuzzCache(BuzzConfig(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.sink, wl.window,
+                                 wl.segment, wl.keep, wl.evict_every, max_context, old_stride=wl.old_stride,
+                                 flags=flags))
+        if splits:
+            c.set_splits(splits)
+        caches.append(c)
+    return caches
+
+
+def prefill_all(wl, caches, device):
+    import torch
+    from workloads import prompt_inputs
+    for layer, c in enumerate(caches):
+        p = prompt_inputs(wl, layer=layer, device=device)
+        n_obs = min(wl.n_obs, wl.prompt)
+        q_obs = p["q_obs"][:, :, p["q_obs"].shape[2] - n_obs:, :].contiguous() if n_obs else None
+        c.prefill(p["K"], p["V"], q_obs=q_obs)
+        torch.cuda.synchronize()
+        del p
+
+
+def run_steps(caches, dec, out, first, count):
+    for t in range(first, first + count):
+        for layer, c in enumerate(caches):
+            d = dec[layer % len(dec)]
+            c.decode_step(d["q"][t], d["k"][t], d["v"][t], out)
+
+
+def cpu_baseline(wl, budget_s=20.0):
+    """The oracle as it stands, on the host cores, on a bounded sample: one layer, every (batch, kv-head) unit,
+    prompt scores left at zero (prefill is not part of the metric), decode steps until the time budget is used."""
+    import numpy as np
+    from oracle.buzz_oracle import OracleCache, OracleConfig, _load
+    from workloads import decode_inputs, prompt_inputs
+    max_units = 64                                     # bound host memory: units are independent and identical in cost
+    B = wl.batch
+    Hkv = wl.n_kv_heads
+    while B * Hkv > max_units and B > 1:
+        B //= 2
+    sub = wl.scaled(batch=B)
+    p = prompt_inputs(sub, device="cpu")
+    steps = min(sub.decode_steps, 4 * sub.evict_every)
+    d = decode_inputs(sub, device="cpu", steps=steps)
+    o = OracleCache(OracleConfig(sub.batch, sub.n_q_heads, sub.n_kv_heads, sub.head_dim, sub.sink, sub.window,
+                                 sub.segment, sub.keep, sub.evict_every, sub.old_stride))
+    o.prefill(p["K"].double().numpy(), p["V"].double().numpy())
+    del p
+    q, k, v = (d[x].double().numpy() for x in ("q", "k", "v"))
+    done, t0 = 0, time.perf_counter()
+    while done < steps and (time.perf_counter() - t0 < budget_s or done < sub.evict_every):
+        o.decode_step(q[done], k[done], v[done])
+        done += 1
+    dt = time.perf_counter() - t0
+    frac = (sub.batch * sub.n_kv_heads) / (wl.batch * wl.n_kv_heads)
+    steps_per_s = done / dt * frac / wl.layers          # scaled to the full batch and layer stack
+    cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or os.cpu_count()
+    return {"value": steps_per_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"1 layer, {sub.batch * sub.n_kv_heads} of {wl.batch * wl.n_kv_heads} (batch, kv-head) units, "
+                      f"{done} decode steps incl. {done // sub.evict_every} evictions, {dt:.1f} s; "
+                      f"scaled by units and {wl.layers} layer(s)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards without communication over layers, "
+              "batch and kv heads); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT
+    from workloads import decode_inputs, get_workload
+
+    wl = get_workload(args.workload)
+    layers = args.layers or wl.layers
+    warmup = args.warmup if args.warmup is not None else min(64, wl.decode_steps // 8)
+    steps = args.steps if args.steps is not None else wl.decode_steps - warmup
+    total = warmup + steps
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+
+    n_streams = min(layers, 4)                          # decode inputs: a few distinct seeded streams, reused over layers
+    dec = [decode_inputs(wl, layer=i, device=device, steps=total) for i in range(n_streams)]
+    out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device=device)
+    caches = make_caches(wl, layers, wl.prompt + total, args.splits, FLAG_AUTO_EVICT)
+    prefill_all(wl, caches, device)
+
+    run_steps(caches, dec, out, 0, warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(caches, dec, out, warmup, steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_end = caches[0].lengths()[0]
+
+    # second pass, same steps, with HIP events around every kernel (on the launch stream)
+    roofline = None
+    extra = {}
+    if not args.no_profile_pass:
+        prefill_all(wl, caches, device)
+        run_steps(caches, dec, out, 0, warmup)
+        for c in caches:
+            c.profile(True)
+        run_steps(caches, dec, out, warmup, steps)
+        torch.cuda.synchronize()
+        prof = [c.profile_read() for c in caches]
+        for c in caches:
+            c.profile(False)
+        launches = sum(p["attn_launches"] for p in prof)
+        attn_ms = sum(p["attn_ms"] for p in prof)
+        epi_ms = sum(p["epilogue_ms"] for p in prof)
+        ev_ms = sum(p["evict_ms"] for p in prof)
+        row_bytes = sum(p["attn_row_bytes"] for p in prof)
+        units = wl.batch * wl.n_kv_heads
+        rows = row_bytes / (units * 2 * wl.head_dim * (4 if wl.dtype == "fp32" else 2))   # sum of n over launches
+        achieved = row_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms else 0.0
+        traffic = None
+        if args.traffic_kib:
+            traffic = {"fetch_bytes": args.traffic_kib[0] * 1024, "write_bytes": args.traffic_kib[1] * 1024}
+        roofline = {"bound": "hbm", "kernel": "attn_split_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                    "avg_launch_us": attn_ms * 1e3 / max(launches, 1),
+                    "bytes_per_launch": row_bytes / max(launches, 1), "traffic": traffic}
+        pass_bytes = row_bytes + units * rows * 8.0                       # + fp32 score read and write per row
+        extra = {"attn_plus_score_gbs": pass_bytes / ((attn_ms + epi_ms) * 1e-3) / 1e9 if attn_ms else 0.0,
+                 "epilogue_avg_us": epi_ms * 1e3 / max(launches, 1),
+                 "evict_avg_us": ev_ms * 1e3 / max(sum(p["evictions"] for p in prof), 1),
+                 "evict_time_over_attn_time": ev_ms / (attn_ms + epi_ms) if attn_ms else 0.0}
+        extra["attn_plus_score_frac"] = extra["attn_plus_score_gbs"] / HBM_PEAK_GBS
+
+    base = None if args.no_cpu_baseline else cpu_baseline(wl)
+    line = {
+        "metric": "decode_steps_per_sec_incl_eviction", "value": steps / elapsed, "unit": "steps/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": f"{wl.dtype} storage, f32 accumulate", "data": "synthetic",
+        "tokens_per_s": steps / elapsed * wl.batch,
+        "config": {"workload": wl.name, "layers": layers, "batch": wl.batch, "n_q_heads": wl.n_q_heads,
+                   "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "prompt": wl.prompt, "sink": wl.sink,
+                   "window": wl.window, "segment": wl.segment, "keep": wl.keep, "evict_every": wl.evict_every,
+                   "old_stride": wl.old_stride, "retained_rows_end": n_end, "splits": args.splits or "auto"},
+        "roofline": roofline, "cpu_baseline": base,
+    }
+    line.update(extra)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,193 @@
+/*
+ * buzz.h -- C ABI of the MI355X (gfx950) BUZZ sparse-KV-cache decode library.
+ *
+ * BUZZ (arxiv 2410.23079) keeps, per attention head, a bounded KV cache made of
+ *   [ k attention-sink tokens | segmented heavy hitters ("old") | buffered new tokens | w window tokens ]
+ * (Sec. 3.3, Fig. 3).  Every decode step appends the new key/value, attends over
+ * all retained rows, and adds the attention probabilities to each row's
+ * accumulated score; once T tokens have left the window, the "beehive"
+ * eviction cuts them into segments of s, keeps the top-scoring row(s) of each
+ * segment, interval-samples the older survivors with stride s^ and packs
+ * the cache (Alg. 1, Alg. 2).
+ *
+ * General conventions
+ *   - One handle = one layer's cache for `batch` sequences of equal length.
+ *     (batch, kv-head) pairs are independent caches (Sec. 3.1 treats one head).
+ *   - All tensor arguments are DEVICE pointers unless a comment says "host".
+ *     They are borrowed until the work enqueued by the call has completed on
+ *     the given stream; nothing is copied to or from the host.
+ *   - Every call only enqueues kernels on `hip_stream` (a hipStream_t cast to
+ *     void*, NULL = the default stream) and returns without synchronising.
+ *     All sizes (rows retained, survivors, offsets) are functions of the
+ *     configuration and the call history alone, so the host never reads back.
+ *   - Returns BUZZ_OK (0) or a negative buzz_status.  Arguments are validated
+ *     before anything is enqueued: a failed call leaves the cache unchanged.
+ *   - A handle must not be used from two threads at once.
+ *   - q, k, v share `kv_dtype`; attention output and scores are fp32.
+ */
+#ifndef BUZZ_H
+#define BUZZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct buzz_cache buzz_cache_t; /* opaque, host memory owned by the library */
+
+typedef enum buzz_status {
+    BUZZ_OK = 0,
+    BUZZ_EINVAL = -1,       /* bad argument or configuration */
+    BUZZ_ECAPACITY = -2,    /* the call would overflow the cache or the workspace */
+    BUZZ_ESTATE = -3,       /* call not valid in the handle's current state */
+    BUZZ_EHIP = -4,         /* a HIP runtime call or kernel launch failed */
+    BUZZ_EUNSUPPORTED = -5  /* valid request the kernels do not cover (shape, dtype) */
+} buzz_status;
+
+enum { BUZZ_FP32 = 0, BUZZ_FP16 = 1, BUZZ_BF16 = 2 };
+
+enum {
+    BUZZ_FLAG_AUTO_EVICT = 1u, /* buzz_decode_step evicts by itself when T new tokens are buffered */
+    BUZZ_FLAG_DRY_RUN = 2u     /* do all host bookkeeping and validation but launch nothing (no GPU needed) */
+};
+
+/* Symbols follow the paper's notation table (Sec. 3.3). */
+typedef struct buzz_config {
+    int32_t batch;        /* sequences per call */
+    int32_t n_q_heads;    /* query heads; multiple of n_kv_heads */
+    int32_t n_kv_heads;   /* key/value heads; the score of a row is summed over its query group */
+    int32_t head_dim;     /* d of eq. 3; 64, 128 or 256 */
+    int32_t kv_dtype;     /* BUZZ_FP32 / BUZZ_FP16 / BUZZ_BF16 */
+    int32_t sink;         /* k : first tokens always kept ("attention sink") */
+    int32_t window;       /* w : most recent tokens always kept ("sliding window") */
+    int32_t segment;      /* s : stride of the segments ("hives") for new tokens; 1..4096 */
+    int32_t keep;         /* rows kept per segment; the paper keeps 1; 0 keeps none (sink + window only) */
+    int32_t evict_every;  /* T : number of tokens buffered outside the window before one eviction */
+    int32_t old_stride;   /* s^: interval-sampling stride for old tokens; 0 => floor((s+1)/2) as in the paper,
+                                 1 => survivors persist */
+    uint32_t flags;       /* BUZZ_FLAG_* */
+    int64_t max_context;  /* upper bound on prompt + decoded tokens; sizes the workspace */
+    int64_t capacity;     /* retained rows per head the cache may hold, = sink + old capacity + window + T;
+                             0 => derived from max_context so that it can never overflow.  With s^ > 1 a
+                             prefill keeps sampling until the rows fit this capacity (Remark 2). */
+    float softmax_scale;  /* 0 => 1/sqrt(head_dim) (eq. 3); the log-n variant of Sec. 3.5 passes
+                             log(n)/log(512)/sqrt(head_dim) */
+    int32_t reserved;     /* must be 0 */
+} buzz_config_t;
+
+/*
+ * Bytes of device workspace a cache with this configuration needs (K and V
+ * arenas, fp32 scores, int32 positions, split-softmax partials, logits,
+ * prefill scratch).  `bytes` is a host pointer.
+ * Errors: BUZZ_EINVAL (null pointer, inconsistent configuration),
+ *         BUZZ_EUNSUPPORTED (head_dim / dtype / group size without a kernel).
+ */
+int buzz_workspace_bytes(const buzz_config_t* cfg, size_t* bytes);
+
+/*
+ * Create a cache over a caller-owned device workspace of at least
+ * buzz_workspace_bytes() bytes, 256-byte aligned.  The workspace must outlive
+ * the handle; the library never frees it.  Touches no device memory.
+ * Errors: as buzz_workspace_bytes, plus BUZZ_ECAPACITY if `bytes` is too small.
+ */
+int buzz_cache_create(const buzz_config_t* cfg, void* dev_workspace, size_t bytes, buzz_cache_t** out);
+
+/*
+ * Load a prompt (eq. 1 gives K, V; the caller did the projections) and bring
+ * the cache to its bounded form (Remark 2).
+ *   k, v        [batch][n_kv_heads][n_prompt][head_dim], kv_dtype
+ *   q_obs       [batch][n_q_heads][n_obs][head_dim]: queries of the last n_obs
+ *               prompt positions (query t sits at position n_prompt-n_obs+t and
+ *               attends causally); their attention probabilities initialise the
+ *               accumulated scores.  NULL with n_obs = 0 for none.
+ *   init_score  [batch][n_kv_heads][n_prompt] fp32 starting scores, or NULL for zeros.
+ * If at least T prompt tokens lie between sink and window they are sampled at
+ * once (all of them count as "new", Alg. 1 with n_old = 0); with s^ > 1 and an
+ * explicit capacity the survivors are interval-sampled again until they fit.
+ * Resets the handle: may be called again to start a new sequence.
+ * Errors: BUZZ_EINVAL, BUZZ_ECAPACITY (n_prompt > max_context, survivors do
+ *         not fit), BUZZ_EHIP.
+ */
+int buzz_prefill(buzz_cache_t* cache, const void* k, const void* v, int64_t n_prompt,
+                 const void* q_obs, int64_t n_obs, const float* init_score, void* hip_stream);
+
+/*
+ * One decode step (eq. 2, eq. 3 / eq. 5, score accumulation):
+ *   append k_new, v_new as a new row (score 0, position = tokens seen so far);
+ *   out[g] = softmax(scale * q[g] . K^T) V over every retained row, the new one included;
+ *   score[row] += sum over the query heads g of the row's kv head of the probabilities;
+ *   with BUZZ_FLAG_AUTO_EVICT, run buzz_evict when T new tokens are buffered (Alg. 1).
+ *   q      [batch][n_q_heads][head_dim], kv_dtype
+ *   k_new  [batch][n_kv_heads][head_dim], kv_dtype       v_new likewise
+ *   out    [batch][n_q_heads][head_dim], fp32
+ * Errors: BUZZ_EINVAL, BUZZ_ESTATE (no prefill yet), BUZZ_ECAPACITY (max_context
+ *         reached, or window + buffer full because eviction was not called), BUZZ_EHIP.
+ */
+int buzz_decode_step(buzz_cache_t* cache, const void* q, const void* k_new, const void* v_new,
+                     float* out, void* hip_stream);
+
+/*
+ * One eviction (Alg. 1 lines 13-19 with Alg. 2): old rows are interval-sampled
+ * with stride s^, the rows between old region and window are cut into
+ * segments of s from their start (the last may be ragged) and the top
+ * min(keep, len) of each segment under (score descending, index ascending;
+ * NaN lowest) survive in index order; K, V, score and position of the survivors
+ * are packed behind the sink.  Does nothing while the cache holds no more than
+ * sink + window rows (Remark 1).  May be called at any time.
+ * Errors: BUZZ_EINVAL, BUZZ_ESTATE, BUZZ_ECAPACITY (survivors exceed the old
+ *         capacity; only possible with many manual partial evictions), BUZZ_EHIP.
+ */
+int buzz_evict(buzz_cache_t* cache, void* hip_stream);
+
+/* Free the host handle (never the workspace).  NULL is allowed. Errors: BUZZ_EINVAL on a stale handle. */
+int buzz_cache_destroy(buzz_cache_t* cache);
+
+/*
+ * Current sizes (host pointers, any may be NULL): n rows retained, n_old rows
+ * in the old region, new_count rows buffered between old region and window.
+ */
+int buzz_cache_len(const buzz_cache_t* cache, int64_t* n, int64_t* n_old, int64_t* new_count);
+
+/*
+ * Copy the retained rows out in cache order [sink | old | new | window]:
+ *   k, v   [batch][n_kv_heads][n][head_dim] kv_dtype;  score [batch][n_kv_heads][n] fp32;
+ *   pos    [batch][n_kv_heads][n] int32 original token index.   Any may be NULL.
+ * Errors: BUZZ_EINVAL, BUZZ_ESTATE, BUZZ_EHIP.
+ */
+int buzz_cache_export(buzz_cache_t* cache, void* k, void* v, float* score, int32_t* pos, void* hip_stream);
+
+/*
+ * Tuning knob: number of key-range splits per (batch, kv-head) used by the
+ * split softmax of the decode kernel; 0 restores the automatic choice.
+ * Errors: BUZZ_EINVAL (negative, or above what the workspace was sized for).
+ */
+int buzz_cache_set_splits(buzz_cache_t* cache, int32_t n_splits);
+
+/*
+ * Benchmark aid: per-kernel device time measured with HIP events recorded on
+ * the stream each kernel is launched on.  buzz_cache_profile(cache, 1) clears
+ * the counters and starts recording (two events around every launch, which
+ * costs a little: use a separate pass for end-to-end timing);
+ * buzz_cache_profile(cache, 0) stops.  buzz_cache_profile_read waits for the
+ * recorded events, then fills `out` (host pointer).
+ * Errors: BUZZ_EINVAL, BUZZ_EHIP.
+ */
+typedef struct buzz_profile {
+    int64_t attn_launches;     /* split decode-attention kernel */
+    int64_t epilogue_launches; /* combine + score-accumulate kernel */
+    int64_t evictions;         /* whole evictions (all their kernels) */
+    double attn_ms, epilogue_ms, evict_ms; /* summed device time */
+    double attn_row_bytes;     /* sum over attn launches of units * rows * 2 * head_dim * sizeof(element) */
+} buzz_profile_t;
+int buzz_cache_profile(buzz_cache_t* cache, int enable);
+int buzz_cache_profile_read(buzz_cache_t* cache, buzz_profile_t* out);
+
+/* Static description of a status code (host string, never NULL). */
+const char* buzz_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BUZZ_H */

@@ -1,0 +1,500 @@
+// Host side of the BUZZ decode library: C ABI, validation, workspace layout and the integer
+// bookkeeping of Alg. 1 (sizes of sink / old / new / window regions).  Every size is a function of
+// the configuration and the call history, so nothing is ever read back from the device.
+#include <math.h>
+#include <new>
+#include <vector>
+
+#include "buzz_internal.h"
+
+using namespace buzz;
+
+namespace {
+
+constexpr uint32_t kMagic = 0xB0220C4Eu;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+struct Layout {
+    size_t K, V, score, pos, logit, part_ml, part_o, sel, stK, stV, stScore, stPos, pscore, obs_stats, total;
+    int32_t cap, old_cap, ring_cap, ring_base, s_cap, sel_stride, st_rows;
+    int32_t units, G, elem, row_bytes, old_stride, keep;
+};
+
+int make_layout(const buzz_config_t* c, Layout* L)
+{
+    if (!c) return BUZZ_EINVAL;
+    if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1) return BUZZ_EINVAL;
+    if (c->n_q_heads % c->n_kv_heads) return BUZZ_EINVAL;
+    if (c->kv_dtype < BUZZ_FP32 || c->kv_dtype > BUZZ_BF16) return BUZZ_EINVAL;
+    if (c->sink < 0 || c->window < 0 || c->segment < 1 || c->keep < 0 || c->evict_every < 1) return BUZZ_EINVAL;
+    if (c->old_stride < 0 || c->max_context < 1 || c->capacity < 0 || c->reserved != 0) return BUZZ_EINVAL;
+    if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN)) return BUZZ_EINVAL;
+    if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BUZZ_EINVAL;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if (!attn_supported(c->kv_dtype, c->head_dim, G)) return BUZZ_EUNSUPPORTED;
+    if (c->segment > kMaxSegment) return BUZZ_EUNSUPPORTED;
+    const int64_t units = (int64_t)c->batch * c->n_kv_heads;
+    if (units > 65535) return BUZZ_EUNSUPPORTED;
+    if (c->max_context > (1 << 28)) return BUZZ_EUNSUPPORTED;
+
+    const int64_t k = c->sink, w = c->window, s = c->segment, T = c->evict_every;
+    const int64_t keep = c->keep < c->segment ? c->keep : c->segment;   // a segment cannot yield more rows than it has
+    const int64_t M = c->max_context > k + w ? c->max_context - k - w : 0;   // tokens that can ever be "new"
+    int64_t old_cap;
+    if (c->capacity > 0) {
+        old_cap = c->capacity - k - w - T;
+        if (old_cap < 0) return BUZZ_EINVAL;
+    } else {
+        const int64_t bound = keep * (ceil_div(M, s) + ceil_div(M, T) + 1);
+        old_cap = keep == 0 ? 0 : (bound < M ? bound : M);
+    }
+    const int64_t ring = w + T;
+    const int64_t cap = (int64_t)align_up((size_t)(k + old_cap + ring), 64);
+    if (cap > (1 << 28)) return BUZZ_EUNSUPPORTED;
+
+    L->units = (int32_t)units;
+    L->G = G;
+    L->elem = c->kv_dtype == BUZZ_FP32 ? 4 : 2;
+    L->row_bytes = c->head_dim * L->elem;
+    L->old_stride = c->old_stride > 0 ? c->old_stride : (c->segment + 1) / 2;
+    L->keep = (int32_t)keep;
+    L->cap = (int32_t)cap;
+    L->old_cap = (int32_t)old_cap;
+    L->ring_cap = (int32_t)ring;
+    L->ring_base = (int32_t)(cap - ring);
+    int64_t s_cap = kMaxBlocks / units;
+    if (s_cap < 1) s_cap = 1;
+    if (s_cap > kMaxSplits) s_cap = kMaxSplits;
+    L->s_cap = (int32_t)s_cap;
+    const int64_t sel_bound = keep * (ceil_div(M, s) + 1);
+    L->sel_stride = (int32_t)(keep == 0 ? 1 : (sel_bound < M ? sel_bound : (M > 0 ? M : 1)));
+    L->st_rows = L->old_stride > 1 ? (int32_t)ceil_div(old_cap, L->old_stride) + 1 : 0;
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+    const size_t rows = (size_t)units * cap;
+    L->K = take(rows * L->row_bytes);
+    L->V = take(rows * L->row_bytes);
+    L->score = take(rows * 4);
+    L->pos = take(rows * 4);
+    L->logit = take(rows * G * 4);
+    L->part_ml = take((size_t)units * s_cap * G * 2 * 4);
+    L->part_o = take((size_t)units * s_cap * G * c->head_dim * 4);
+    L->sel = take((size_t)units * L->sel_stride * 4);
+    const size_t strows = (size_t)units * L->st_rows;
+    L->stK = take(strows * L->row_bytes);
+    L->stV = take(strows * L->row_bytes);
+    L->stScore = take(strows * 4);
+    L->stPos = take(strows * 4);
+    L->pscore = take((size_t)units * c->max_context * 4);
+    L->obs_stats = take((size_t)units * ceil_div(c->max_context, kObsKeyBlock) * kObsRows * 2 * 4);
+    L->total = off;
+    return BUZZ_OK;
+}
+
+}  // namespace
+
+struct buzz_cache {
+    uint32_t magic;
+    buzz_config_t cfg;
+    Layout L;
+    char* ws;
+    float scale;
+    bool dry;
+    // state (Alg. 1): n = sink_filled + n_old + tail
+    bool ready;
+    int64_t sink_filled, n_old, tail, head, tokens_seen;
+    int32_t user_splits;
+    // benchmark profiling: event pairs per kernel class (0 attn, 1 epilogue, 2 eviction)
+    bool prof;
+    std::vector<hipEvent_t> ev[3];
+    double prof_row_bytes;
+
+    int64_t n() const { return sink_filled + n_old + tail; }
+    int64_t new_count() const
+    {
+        const int64_t v = n() - cfg.sink - n_old - cfg.window;
+        return v > 0 ? v : 0;
+    }
+    RingMap map() const
+    {
+        RingMap m;
+        m.front = (int32_t)(sink_filled + n_old);
+        m.ring_base = L.ring_base;
+        m.ring_head = (int32_t)head;
+        m.ring_cap = L.ring_cap;
+        return m;
+    }
+    template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+namespace {
+
+inline bool alive(const buzz_cache_t* c) { return c && c->magic == kMagic; }
+
+constexpr size_t kMaxProfEvents = 1 << 15;
+
+// records an event on `st` for kernel class `cls` while profiling is on
+inline void prof_mark(buzz_cache_t* c, int cls, hipStream_t st)
+{
+    if (!c->prof || c->ev[cls].size() >= kMaxProfEvents) return;
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    if (hipEventRecord(e, st) != hipSuccess) { (void)hipEventDestroy(e); return; }
+    c->ev[cls].push_back(e);
+}
+
+void prof_clear(buzz_cache_t* c)
+{
+    for (auto& v : c->ev) {
+        for (hipEvent_t e : v) (void)hipEventDestroy(e);
+        v.clear();
+    }
+    c->prof_row_bytes = 0.0;
+}
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? BUZZ_OK : BUZZ_EHIP; }
+
+GatherArgs cache_gather_base(const buzz_cache_t* c)
+{
+    GatherArgs g{};
+    g.srcK = c->at<char>(c->L.K); g.srcV = c->at<char>(c->L.V);
+    g.srcScore = c->at<float>(c->L.score); g.srcPos = c->at<int32_t>(c->L.pos);
+    g.src_unit_rows = c->L.cap;
+    g.src_step = 1; g.sel_step = 1;
+    g.dstK = c->at<char>(c->L.K); g.dstV = c->at<char>(c->L.V);
+    g.dstScore = c->at<float>(c->L.score); g.dstPos = c->at<int32_t>(c->L.pos);
+    g.dst_unit_rows = c->L.cap;
+    g.row_bytes = c->L.row_bytes;
+    return g;
+}
+
+// Alg. 1 lines 13-19 on the current state.
+int evict_impl(buzz_cache_t* c, hipStream_t st)
+{
+    const buzz_config_t& cfg = c->cfg;
+    const Layout& L = c->L;
+    const int64_t k = cfg.sink, w = cfg.window, s = cfg.segment, keep = L.keep;
+    if (c->n() <= k + w) return BUZZ_OK;                       // Remark 1
+    const int64_t newc = c->new_count();
+    const int64_t sh = L.old_stride;
+    const int64_t old2 = ceil_div(c->n_old, sh);               // interval sampling keeps offsets 0, s^, 2 s^, ...
+    const int64_t take_last = newc % s < keep ? newc % s : keep;
+    const int64_t new2 = keep * (newc / s) + take_last;        // every segment yields min(keep, len)
+    if (old2 + new2 > L.old_cap) return BUZZ_ECAPACITY;
+    if (!c->dry) {
+        prof_mark(c, 2, st);
+        if (old2 < c->n_old) {                                 // thin the old region through the staging rows
+            GatherArgs g = cache_gather_base(c);
+            g.src_start = (int32_t)k; g.src_step = (int32_t)sh;
+            g.dstK = c->at<char>(L.stK); g.dstV = c->at<char>(L.stV);
+            g.dstScore = c->at<float>(L.stScore); g.dstPos = c->at<int32_t>(L.stPos);
+            g.dst_unit_rows = L.st_rows; g.dst_start = 0; g.n_rows = (int32_t)old2;
+            if (hipError_t e = launch_gather_rows(g, L.units, st)) return hip_rc(e);
+            GatherArgs b = cache_gather_base(c);
+            b.srcK = c->at<char>(L.stK); b.srcV = c->at<char>(L.stV);
+            b.srcScore = c->at<float>(L.stScore); b.srcPos = c->at<int32_t>(L.stPos);
+            b.src_unit_rows = L.st_rows; b.src_start = 0; b.src_step = 1;
+            b.dst_start = (int32_t)k; b.n_rows = (int32_t)old2;
+            if (hipError_t e = launch_gather_rows(b, L.units, st)) return hip_rc(e);
+        }
+        if (new2 > 0) {
+            SelectArgs sa{};
+            sa.score = c->at<float>(L.score); sa.unit_stride = L.cap;
+            sa.map = c->map(); sa.lo = sa.map.front; sa.new_count = (int32_t)newc;
+            sa.segment = cfg.segment; sa.keep = L.keep;
+            sa.sel = c->at<int32_t>(L.sel); sa.sel_stride = L.sel_stride;
+            if (hipError_t e = launch_segment_topk(sa, L.units, st)) return hip_rc(e);
+            GatherArgs g = cache_gather_base(c);
+            g.src_map = c->map();
+            g.sel = c->at<int32_t>(L.sel); g.sel_stride = L.sel_stride; g.sel_start = 0; g.sel_step = 1;
+            g.dst_start = (int32_t)(k + old2); g.n_rows = (int32_t)new2;
+            if (hipError_t e = launch_gather_rows(g, L.units, st)) return hip_rc(e);
+        }
+        prof_mark(c, 2, st);
+    }
+    c->n_old = old2 + new2;
+    c->head = (c->head + newc) % L.ring_cap;
+    c->tail -= newc;
+    return BUZZ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int buzz_workspace_bytes(const buzz_config_t* cfg, size_t* bytes)
+{
+    if (!cfg || !bytes) return BUZZ_EINVAL;
+    Layout L;
+    if (int rc = make_layout(cfg, &L)) return rc;
+    *bytes = L.total;
+    return BUZZ_OK;
+}
+
+int buzz_cache_create(const buzz_config_t* cfg, void* dev_workspace, size_t bytes, buzz_cache_t** out)
+{
+    if (!cfg || !out) return BUZZ_EINVAL;
+    Layout L;
+    if (int rc = make_layout(cfg, &L)) return rc;
+    const bool dry = cfg->flags & BUZZ_FLAG_DRY_RUN;
+    if (!dry) {
+        if (!dev_workspace || ((uintptr_t)dev_workspace & 255)) return BUZZ_EINVAL;
+        if (bytes < L.total) return BUZZ_ECAPACITY;
+    }
+    buzz_cache_t* c = new (std::nothrow) buzz_cache_t();
+    if (!c) return BUZZ_EINVAL;
+    c->magic = kMagic;
+    c->cfg = *cfg;
+    c->L = L;
+    c->ws = (char*)dev_workspace;
+    c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+    c->dry = dry;
+    c->ready = false;
+    c->sink_filled = c->n_old = c->tail = c->head = c->tokens_seen = 0;
+    c->user_splits = 0;
+    c->prof = false;
+    c->prof_row_bytes = 0.0;
+    *out = c;
+    return BUZZ_OK;
+}
+
+int buzz_cache_destroy(buzz_cache_t* c)
+{
+    if (!c) return BUZZ_OK;
+    if (!alive(c)) return BUZZ_EINVAL;
+    prof_clear(c);
+    c->magic = 0;
+    delete c;
+    return BUZZ_OK;
+}
+
+int buzz_cache_len(const buzz_cache_t* c, int64_t* n, int64_t* n_old, int64_t* new_count)
+{
+    if (!alive(c)) return BUZZ_EINVAL;
+    if (n) *n = c->n();
+    if (n_old) *n_old = c->n_old;
+    if (new_count) *new_count = c->new_count();
+    return BUZZ_OK;
+}
+
+int buzz_cache_set_splits(buzz_cache_t* c, int32_t n_splits)
+{
+    if (!alive(c) || n_splits < 0 || n_splits > c->L.s_cap) return BUZZ_EINVAL;
+    c->user_splits = n_splits;
+    return BUZZ_OK;
+}
+
+int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, const void* q_obs, int64_t n_obs,
+                 const float* init_score, void* hip_stream)
+{
+    if (!alive(c)) return BUZZ_EINVAL;
+    if (N < 0 || n_obs < 0 || n_obs > N) return BUZZ_EINVAL;
+    if (N > 0 && !c->dry && (!kp || !vp)) return BUZZ_EINVAL;
+    if ((n_obs > 0) != (q_obs != nullptr) && !c->dry) return BUZZ_EINVAL;
+    const buzz_config_t& cfg = c->cfg;
+    const Layout& L = c->L;
+    if (N > cfg.max_context) return BUZZ_ECAPACITY;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t k = cfg.sink, w = cfg.window, s = cfg.segment, keep = L.keep, T = cfg.evict_every;
+    const int64_t M = N - k - w;                                // prompt tokens between sink and window
+    const bool sample = M >= T;
+    int64_t survivors = 0, sel_step = 1;
+    if (sample) {
+        const int64_t last = M % s < keep ? M % s : keep;
+        survivors = keep * (M / s) + last;
+        if (L.old_stride > 1 && cfg.capacity > 0) {            // Remark 2: keep sampling until it fits
+            while (survivors > L.old_cap) {
+                const int64_t nxt = ceil_div(survivors, L.old_stride);
+                if (nxt >= survivors) return BUZZ_ECAPACITY;
+                survivors = nxt;
+                sel_step *= L.old_stride;
+            }
+        }
+        if (survivors > L.old_cap) return BUZZ_ECAPACITY;
+    }
+    const int64_t sink_rows = N < k ? N : k;
+    const int64_t tail_rows = sample ? w : N - sink_rows;
+    if (tail_rows > L.ring_cap) return BUZZ_ECAPACITY;
+
+    if (!c->dry) {
+        float* ps = c->at<float>(L.pscore);
+        // starting scores, one row of N per unit
+        if (hipError_t e = launch_fill_f32(ps, init_score, (int64_t)L.units * N, st)) return hip_rc(e);
+        if (n_obs > 0) {
+            const int G = L.G;
+            const int max_q = kObsRows / G;                // queries per pass
+            for (int64_t t0 = 0; t0 < n_obs; t0 += max_q) {
+                ObsArgs oa{};
+                oa.K = kp; oa.q_obs = q_obs; oa.score = ps; oa.stats = c->at<float>(L.obs_stats);
+                oa.N = (int32_t)N; oa.n_obs = (int32_t)n_obs;
+                oa.t_begin = (int32_t)t0; oa.t_count = (int32_t)((n_obs - t0) < max_q ? (n_obs - t0) : max_q);
+                oa.Hq = cfg.n_q_heads; oa.Hkv = cfg.n_kv_heads;
+                oa.scale_log2 = c->scale * 1.4426950408889634f;
+                if (hipError_t e = launch_obs_scores(cfg.kv_dtype, cfg.head_dim, G, oa, L.units, st)) return hip_rc(e);
+            }
+        }
+        GatherArgs g{};
+        g.srcK = kp; g.srcV = vp; g.srcScore = ps; g.srcPos = nullptr;
+        g.src_unit_rows = N; g.src_step = 1; g.sel_step = 1;
+        g.dstK = c->at<char>(L.K); g.dstV = c->at<char>(L.V);
+        g.dstScore = c->at<float>(L.score); g.dstPos = c->at<int32_t>(L.pos);
+        g.dst_unit_rows = L.cap; g.row_bytes = L.row_bytes;
+        // sink
+        GatherArgs gs = g;
+        gs.src_start = 0; gs.dst_start = 0; gs.n_rows = (int32_t)sink_rows;
+        if (hipError_t e = launch_gather_rows(gs, L.units, st)) return hip_rc(e);
+        if (sample) {
+            if (survivors > 0) {
+                SelectArgs sa{};
+                sa.score = ps; sa.unit_stride = N;
+                sa.map = RingMap{0, 0, 0, 0};
+                sa.lo = (int32_t)k; sa.new_count = (int32_t)M;
+                sa.segment = cfg.segment; sa.keep = L.keep;
+                sa.sel = c->at<int32_t>(L.sel); sa.sel_stride = L.sel_stride;
+                if (hipError_t e = launch_segment_topk(sa, L.units, st)) return hip_rc(e);
+                GatherArgs gv = g;
+                gv.sel = c->at<int32_t>(L.sel); gv.sel_stride = L.sel_stride; gv.sel_start = 0;
+                gv.sel_step = (int32_t)sel_step;
+                gv.dst_start = (int32_t)k; gv.n_rows = (int32_t)survivors;
+                if (hipError_t e = launch_gather_rows(gv, L.units, st)) return hip_rc(e);
+            }
+            GatherArgs gw = g;
+            gw.src_start = (int32_t)(N - w); gw.dst_start = L.ring_base; gw.n_rows = (int32_t)w;
+            if (hipError_t e = launch_gather_rows(gw, L.units, st)) return hip_rc(e);
+        } else {
+            GatherArgs gt = g;
+            gt.src_start = (int32_t)sink_rows; gt.dst_start = L.ring_base; gt.n_rows = (int32_t)tail_rows;
+            if (hipError_t e = launch_gather_rows(gt, L.units, st)) return hip_rc(e);
+        }
+    }
+    c->sink_filled = sink_rows;
+    c->n_old = survivors;
+    c->tail = tail_rows;
+    c->head = 0;
+    c->tokens_seen = N;
+    c->ready = true;
+    return BUZZ_OK;
+}
+
+int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const void* v_new, float* out,
+                     void* hip_stream)
+{
+    if (!alive(c)) return BUZZ_EINVAL;
+    if (!c->dry && (!q || !k_new || !v_new || !out)) return BUZZ_EINVAL;
+    if (!c->ready) return BUZZ_ESTATE;
+    const buzz_config_t& cfg = c->cfg;
+    const Layout& L = c->L;
+    if (c->tokens_seen >= cfg.max_context) return BUZZ_ECAPACITY;
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    const bool to_sink = c->sink_filled < cfg.sink && c->n_old == 0 && c->tail == 0;   // Remark 1: sink first
+    if (!to_sink && c->tail >= L.ring_cap) return BUZZ_ECAPACITY;
+    const int64_t new_phys = to_sink ? c->sink_filled : L.ring_base + (c->head + c->tail) % L.ring_cap;
+    // state after the append of eq. 2
+    const int64_t sink_filled = c->sink_filled + (to_sink ? 1 : 0);
+    const int64_t tail = c->tail + (to_sink ? 0 : 1);
+    const int64_t n = sink_filled + c->n_old + tail;
+
+    if (!c->dry) {
+        AttnArgs a{};
+        a.q = q; a.k_new = k_new; a.v_new = v_new;
+        a.K = c->at<char>(L.K); a.V = c->at<char>(L.V);
+        a.score = c->at<float>(L.score); a.pos = c->at<int32_t>(L.pos);
+        a.logit = c->at<float>(L.logit); a.part_ml = c->at<float>(L.part_ml); a.part_o = c->at<float>(L.part_o);
+        a.out = out;
+        a.map = c->map();
+        a.map.front = (int32_t)(sink_filled + c->n_old);
+        a.n = (int32_t)n;
+        a.new_phys = (int32_t)new_phys;
+        a.new_pos = (int32_t)c->tokens_seen;
+        a.cap = L.cap;
+        a.Hq = cfg.n_q_heads; a.Hkv = cfg.n_kv_heads;
+        a.s_cap = L.s_cap;
+        a.scale_log2 = c->scale * 1.4426950408889634f;
+        const int tile = attn_tile_rows(cfg.kv_dtype, cfg.head_dim, L.G);
+        int64_t S = c->user_splits > 0 ? c->user_splits : (kTargetBlocks + L.units / 2) / L.units;
+        if (S < 1) S = 1;
+        if (S > L.s_cap) S = L.s_cap;
+        int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
+        a.rows_per_split = (int32_t)rps;
+        a.n_splits = (int32_t)ceil_div(n, rps);
+        prof_mark(c, 0, st);
+        if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st)) return hip_rc(e);
+        prof_mark(c, 0, st);
+        if (c->prof) c->prof_row_bytes += (double)L.units * (double)n * 2.0 * L.row_bytes;
+        prof_mark(c, 1, st);
+        if (hipError_t e = launch_combine_score(cfg.head_dim, L.G, a, L.units, st)) return hip_rc(e);
+        prof_mark(c, 1, st);
+    }
+    c->sink_filled = sink_filled;
+    c->tail = tail;
+    c->tokens_seen += 1;
+    if ((cfg.flags & BUZZ_FLAG_AUTO_EVICT) && c->new_count() >= cfg.evict_every) return evict_impl(c, st);
+    return BUZZ_OK;
+}
+
+int buzz_evict(buzz_cache_t* c, void* hip_stream)
+{
+    if (!alive(c)) return BUZZ_EINVAL;
+    if (!c->ready) return BUZZ_ESTATE;
+    return evict_impl(c, (hipStream_t)hip_stream);
+}
+
+int buzz_cache_export(buzz_cache_t* c, void* k, void* v, float* score, int32_t* pos, void* hip_stream)
+{
+    if (!alive(c)) return BUZZ_EINVAL;
+    if (!c->ready) return BUZZ_ESTATE;
+    if (c->dry) return BUZZ_OK;
+    GatherArgs g = cache_gather_base(c);
+    g.src_map = c->map();
+    g.src_start = 0; g.src_step = 1;
+    g.dstK = k; g.dstV = v; g.dstScore = score; g.dstPos = pos;
+    g.dst_unit_rows = c->n(); g.dst_start = 0; g.n_rows = (int32_t)c->n();
+    return hip_rc(launch_gather_rows(g, c->L.units, (hipStream_t)hip_stream));
+}
+
+int buzz_cache_profile(buzz_cache_t* c, int enable)
+{
+    if (!alive(c)) return BUZZ_EINVAL;
+    if (enable) prof_clear(c);
+    c->prof = enable != 0 && !c->dry;
+    return BUZZ_OK;
+}
+
+int buzz_cache_profile_read(buzz_cache_t* c, buzz_profile_t* out)
+{
+    if (!alive(c) || !out) return BUZZ_EINVAL;
+    double ms[3] = {0, 0, 0};
+    int64_t cnt[3] = {0, 0, 0};
+    for (int cls = 0; cls < 3; ++cls) {
+        const auto& v = c->ev[cls];
+        for (size_t i = 0; i + 1 < v.size(); i += 2) {
+            if (hipEventSynchronize(v[i + 1]) != hipSuccess) return BUZZ_EHIP;
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, v[i], v[i + 1]) != hipSuccess) return BUZZ_EHIP;
+            ms[cls] += t;
+            cnt[cls] += 1;
+        }
+    }
+    out->attn_launches = cnt[0]; out->epilogue_launches = cnt[1]; out->evictions = cnt[2];
+    out->attn_ms = ms[0]; out->epilogue_ms = ms[1]; out->evict_ms = ms[2];
+    out->attn_row_bytes = c->prof_row_bytes;
+    return BUZZ_OK;
+}
+
+const char* buzz_strerror(int status)
+{
+    switch (status) {
+        case BUZZ_OK: return "ok";
+        case BUZZ_EINVAL: return "invalid argument or configuration";
+        case BUZZ_ECAPACITY: return "cache or workspace capacity exceeded";
+        case BUZZ_ESTATE: return "call not valid in the current state (prefill first)";
+        case BUZZ_EHIP: return "HIP runtime error";
+        case BUZZ_EUNSUPPORTED: return "shape, dtype or parameter not covered by the kernels";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,113 @@
+// Internal declarations shared by the host API and the HIP kernels of the BUZZ decode library.
+//
+// Physical layout of one (batch, kv-head) unit, `cap` rows:
+//
+//     [ sink k | old region (old_cap rows, grows upward) | ring of R = w + T rows ]
+//       0        k                                          ring_base = cap - R
+//
+// Attention is invariant under a permutation of the cache rows (eq. 3 is a sum over rows), so
+// the "new + window" tail of the paper's cache order lives in a ring: a decode step appends at
+// the ring's tail, an eviction copies the survivors of the oldest tail rows to the end of the
+// old region and advances the ring head.  The window never moves.  Logical (paper) order is
+//     row j <  front : physical row j                      (front = sink rows filled + n_old)
+//     row j >= front : physical row ring_base + (head + j - front) mod R
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "buzz.h"
+
+namespace buzz {
+
+constexpr int kMaxSplits = 128;        // upper bound on key-range splits per unit
+constexpr int kTargetBlocks = 1024;    // automatic split choice aims at this many blocks per launch
+constexpr int kMaxBlocks = 4096;       // partial buffers are sized for units * splits <= this (or 1 split per unit)
+constexpr int kMaxSegment = 4096;      // segment scores of one wave must fit its LDS slice
+
+struct RingMap {
+    int32_t front;      // rows [0, front) are stored linearly
+    int32_t ring_base;  // first physical row of the ring
+    int32_t ring_head;  // ring offset of logical row `front`
+    int32_t ring_cap;   // R
+    __host__ __device__ inline int32_t phys(int32_t j) const {
+        if (j < front) return j;
+        int32_t r = ring_head + (j - front);
+        if (r >= ring_cap) r -= ring_cap;
+        return ring_base + r;
+    }
+};
+
+struct AttnArgs {
+    const void* q;       // [B][Hq][D]
+    const void* k_new;   // [B][Hkv][D]
+    const void* v_new;
+    void* K;             // [units][cap][D]
+    void* V;
+    float* score;        // [units][cap]
+    int32_t* pos;        // [units][cap]
+    float* logit;        // [units][cap][G]  scaled logits in log2 units, written by the split kernel
+    float* part_ml;      // [units][s_cap][G][2]  (running max, running sum) per split
+    float* part_o;       // [units][s_cap][G][D]  unnormalised partial outputs per split
+    float* out;          // [B][Hq][D]
+    RingMap map;
+    int32_t n;           // retained rows including the one being appended (logical index n-1)
+    int32_t new_phys;    // physical row the appended token is written to
+    int32_t new_pos;     // its original token index
+    int32_t cap;
+    int32_t rows_per_split;
+    int32_t n_splits;
+    int32_t s_cap;
+    int32_t Hq, Hkv;
+    float scale_log2;    // softmax scale * log2(e)
+};
+
+struct SelectArgs {
+    const float* score;        // base of the score array the segments live in
+    int64_t unit_stride;       // elements between units in `score`
+    RingMap map;               // mapping of logical rows (ring_cap == 0: identity)
+    int32_t lo;                // logical index of the first new row
+    int32_t new_count;         // rows to segment
+    int32_t segment, keep;
+    int32_t* sel;              // [units][sel_stride] logical source rows of the survivors, increasing
+    int32_t sel_stride;
+};
+
+struct GatherArgs {
+    const void* srcK; const void* srcV; const float* srcScore; const int32_t* srcPos;  // srcPos NULL => pos = source row
+    int64_t src_unit_rows;     // rows between units in the source arrays
+    RingMap src_map;           // ring_cap == 0: identity
+    const int32_t* sel;        // NULL => affine source rows
+    int32_t sel_stride, sel_start, sel_step;
+    int32_t src_start, src_step;
+    void* dstK; void* dstV; float* dstScore; int32_t* dstPos;    // any may be NULL
+    int64_t dst_unit_rows;
+    int32_t dst_start;
+    int32_t n_rows;
+    int32_t row_bytes;         // D * sizeof(element)
+};
+
+struct ObsArgs {               // prefill scoring: causal attention of observed prompt queries (one pass)
+    const void* K;             // [units][N][D]
+    const void* q_obs;         // [B][Hq][n_obs][D]; query t sits at prompt position N - n_obs + t
+    float* score;              // [units][N]   accumulated in place
+    float* stats;              // [units][key_blocks][kObsRows][2] per key-block (max, sum) of every query row
+    int32_t N, n_obs;
+    int32_t t_begin, t_count;  // queries scored by this pass; t_count * G <= kObsRows
+    int32_t Hq, Hkv;
+    float scale_log2;
+};
+
+constexpr int kObsRows = 256;        // query rows (query x group member) per pass = threads per block
+constexpr int kObsKeyBlock = 1024;   // keys per block of the row-statistics kernel
+
+hipError_t launch_attn_split(int dtype, int D, int G, const AttnArgs& a, int units, hipStream_t st);
+hipError_t launch_combine_score(int D, int G, const AttnArgs& a, int units, hipStream_t st);
+hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st);
+hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st);
+hipError_t launch_fill_f32(float* dst, const float* src, int64_t n, hipStream_t st);  // src NULL => zeros
+hipError_t launch_obs_scores(int dtype, int D, int G, const ObsArgs& a, int units, hipStream_t st);
+int attn_tile_rows(int dtype, int D, int G);   // rows one block consumes per loop trip (split sizes are multiples)
+bool attn_supported(int dtype, int D, int G);
+
+}  // namespace buzz

@@ -1,0 +1,118 @@
+// BeeHive eviction kernels (Sec. 3.3; Alg. 1 lines 13-19, Alg. 2):
+//   segment_topk : one wavefront per (segment, unit) ranks the segment's accumulated scores and
+//                  emits the top min(keep, len) rows in index order (ties -> lowest index, NaN lowest);
+//   gather_rows  : packs K, V, score and position of selected rows into their destination
+//                  (survivors behind the old region, sink / window at prefill, export in cache order).
+// Every segment yields min(keep, len) rows, so a survivor's destination is
+// segment * keep + (rank among the segment's survivors): a wave-level prefix sum over the keep mask.
+#include "buzz_internal.h"
+
+namespace buzz {
+namespace {
+
+constexpr int kSelWaves = 4;
+
+__global__ __launch_bounds__(256) void segment_topk_kernel(const SelectArgs a)
+{
+    extern __shared__ float lds[];                 // [kSelWaves][segment]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seg = blockIdx.x * kSelWaves + wave, unit = blockIdx.y;
+    const int n_seg = (a.new_count + a.segment - 1) / a.segment;
+    const bool active = seg < n_seg;
+    const int start = seg * a.segment;
+    const int len = active ? min(a.segment, a.new_count - start) : 0;
+    const int take = min(a.keep, len);
+    float* sc = lds + wave * a.segment;
+    const float* base = a.score + (size_t)unit * a.unit_stride;
+    for (int e = lane; e < len; e += 64) {
+        const int row = a.lo + start + e;
+        float v = base[a.map.ring_cap ? a.map.phys(row) : row];
+        if (v != v) v = -INFINITY;                 // NaN ranks below everything
+        sc[e] = v;
+    }
+    __syncthreads();
+    if (!active) return;
+    int running = 0;
+    for (int e0 = 0; e0 < len; e0 += 64) {
+        const int e = e0 + lane;
+        bool kp = false;
+        if (e < len) {
+            const float v = sc[e];
+            int before = 0;                        // rows of the segment that rank strictly before row e
+            for (int i = 0; i < len; ++i) {
+                const float vi = sc[i];
+                before += (vi > v) || (vi == v && i < e);
+            }
+            kp = before < take;
+        }
+        const unsigned long long mask = __ballot(kp);
+        if (kp) {
+            const int r = running + __popcll(mask & ((1ull << lane) - 1ull));
+            a.sel[(size_t)unit * a.sel_stride + seg * a.keep + r] = a.lo + start + e;
+        }
+        running += __popcll(mask);
+    }
+}
+
+constexpr int kGatherRowsPerBlock = 64;
+
+__global__ __launch_bounds__(256) void gather_rows_kernel(const GatherArgs a)
+{
+    const int unit = blockIdx.y, tid = threadIdx.x;
+    const int lpr = a.row_bytes >> 4;              // 16-byte lanes per row
+    const int c = tid % lpr, rr = tid / lpr, rows_per_pass = 256 / lpr;
+    const int rbeg = blockIdx.x * kGatherRowsPerBlock;
+    const int rend = min(a.n_rows, rbeg + kGatherRowsPerBlock);
+    const size_t sbase = (size_t)unit * a.src_unit_rows, dbase = (size_t)unit * a.dst_unit_rows;
+    for (int r = rbeg + rr; r < rend; r += rows_per_pass) {
+        const int src = a.sel ? a.sel[(size_t)unit * a.sel_stride + a.sel_start + (size_t)r * a.sel_step]
+                              : a.src_start + r * a.src_step;
+        const int sp = a.src_map.ring_cap ? a.src_map.phys(src) : src;
+        const size_t so = (sbase + sp) * a.row_bytes + c * 16;
+        const size_t dro = dbase + a.dst_start + r;
+        const size_t dof = dro * a.row_bytes + c * 16;
+        if (a.dstK) *(uint4*)((char*)a.dstK + dof) = *(const uint4*)((const char*)a.srcK + so);
+        if (a.dstV) *(uint4*)((char*)a.dstV + dof) = *(const uint4*)((const char*)a.srcV + so);
+        if (c == 0) {
+            if (a.dstScore) a.dstScore[dro] = a.srcScore[sbase + sp];
+            if (a.dstPos) a.dstPos[dro] = a.srcPos ? a.srcPos[sbase + sp] : src;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_f32_kernel(float* dst, const float* src, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src ? src[i] : 0.f;
+}
+
+}  // namespace
+
+hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st)
+{
+    const int n_seg = (a.new_count + a.segment - 1) / a.segment;
+    if (n_seg <= 0) return hipSuccess;
+    dim3 grid((n_seg + kSelWaves - 1) / kSelWaves, units), block(256);
+    const size_t lds = (size_t)kSelWaves * a.segment * sizeof(float);
+    hipLaunchKernelGGL(segment_topk_kernel, grid, block, lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st)
+{
+    if (a.n_rows <= 0) return hipSuccess;
+    dim3 grid((a.n_rows + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock, units), block(256);
+    hipLaunchKernelGGL(gather_rows_kernel, grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float* dst, const float* src, int64_t n, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, dst, src, n);
+    return hipGetLastError();
+}
+
+}  // namespace buzz

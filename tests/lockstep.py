@@ -1,0 +1,162 @@
+"""Lock-step comparison of the HIP library with the CPU oracle on one workload (test helper).
+
+Protocol.  Both sides receive the same tensors.  Attention outputs and accumulated scores are compared
+numerically at every step.  The retained index sets must be bit-exact, and because a selection decided
+by fp32 scores can legitimately differ from one decided by fp64 scores at a near-tie, the selection on
+both sides runs on the same fp32 score array: before every eviction the oracle adopts the scores the
+GPU exported (after they have been checked against its own), then both evict, then the retained
+positions, K rows and V rows are compared exactly.  The prompt scores are handled the same way: they
+are computed once by the library's prefill scoring (a cache configured so that nothing is evicted),
+checked against the oracle's, and handed to both sides as starting scores.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle.buzz_oracle import OracleCache, OracleConfig
+from paper_2410_23079_amd import FLAG_AUTO_EVICT, BuzzCache, BuzzConfig
+from workloads import Workload
+
+OUT_TOL = 2e-3      # contract: max |o - o_ref| / max |o_ref| per (batch, head) vector
+OUT_EXPECT = 1e-4   # what fp32 accumulation over exactly widened inputs should reach (regression guard)
+SCORE_TOL = 1e-4    # relative to max(1, |score|)
+
+
+def buzz_config(wl: Workload, flags=0, max_context=None, **over) -> BuzzConfig:
+    kw = dict(batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
+              kv_dtype=wl.dtype, sink=wl.sink, window=wl.window, segment=wl.segment, keep=wl.keep,
+              evict_every=wl.evict_every, old_stride=wl.old_stride, flags=flags,
+              max_context=max_context or wl.max_context)
+    kw.update(over)
+    return BuzzConfig(**kw)
+
+
+def oracle_config(wl: Workload, n_units: int, **over) -> OracleConfig:
+    kw = dict(batch=n_units, n_q_heads=wl.group, n_kv_heads=1, head_dim=wl.head_dim, sink=wl.sink,
+              window=wl.window, segment=wl.segment, keep=wl.keep, evict_every=wl.evict_every,
+              old_stride=wl.old_stride, auto_evict=False)
+    kw.update(over)
+    return OracleConfig(**kw)
+
+
+def unit_slices(t: torch.Tensor, units, heads_per_unit: int):
+    """[B,H,...] -> float64 numpy [len(units), heads_per_unit, ...] for the chosen (batch, kv-head) units."""
+    rows = [t[b, h * heads_per_unit:(h + 1) * heads_per_unit] for b, h in units]
+    return torch.stack(rows).double().cpu().numpy()
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max over vectors (last axis) of max|got-ref| / max|ref|."""
+    num = np.abs(got - ref).max(axis=-1)
+    den = np.maximum(np.abs(ref).max(axis=-1), 1e-30)
+    return float((num / den).max())
+
+
+def score_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max |got-ref| / max(1, |ref|); 0 for empty arrays."""
+    if got.size == 0:
+        return 0.0
+    return float((np.abs(got - ref) / np.maximum(1.0, np.abs(ref))).max())
+
+
+def gpu_prompt_scores(wl: Workload, prompt, n_obs: int):
+    """Prompt scores from the library's own prefill scoring, with a window so large nothing is evicted."""
+    N = prompt["K"].shape[2]
+    cfg = buzz_config(wl, max_context=N + 1, sink=0, window=N + 1, keep=1, old_stride=1)
+    c = BuzzCache(cfg)
+    q_obs = prompt["q_obs"][:, :, prompt["q_obs"].shape[2] - n_obs:, :].contiguous() if n_obs else None
+    c.prefill(prompt["K"], prompt["V"], q_obs=q_obs)
+    _, _, score, pos = c.export()
+    assert (pos.cpu().numpy() == np.arange(N)).all()
+    c.close()
+    return score
+
+
+def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=None, splits=0,
+                 check_auto=True, capacity=0):
+    """Returns a dict of the worst errors seen; raises AssertionError on any parity failure."""
+    G, D = wl.group, wl.head_dim
+    N = prompt["K"].shape[2]
+    steps = decode["q"].shape[0] if steps is None else steps
+    n_obs = min(wl.n_obs, N) if n_obs is None else n_obs
+    if units is None:
+        units = [(b, h) for b in range(wl.batch) for h in range(wl.n_kv_heads)]
+    U = len(units)
+    uidx_b = torch.tensor([b for b, _ in units])
+    uidx_h = torch.tensor([h for _, h in units])
+    stats = dict(out=0.0, score=0.0, prefill_score=0.0, evictions=0)
+
+    # ---- prompt scores: library vs oracle, then shared
+    Kp, Vp = unit_slices(prompt["K"], units, 1), unit_slices(prompt["V"], units, 1)
+    o_probe = OracleCache(oracle_config(wl, U, sink=0, window=N + 1, old_stride=1))
+    q_obs_u = unit_slices(prompt["q_obs"][:, :, prompt["q_obs"].shape[2] - n_obs:, :], units, G) if n_obs else None
+    o_probe.prefill(Kp, Vp, q_obs=q_obs_u)
+    ref_ps = o_probe.export()[2][:, 0]                                   # [U,N]
+    ps = gpu_prompt_scores(wl, prompt, n_obs)                            # [B,Hkv,N] fp32 on GPU
+    got_ps = ps[uidx_b, uidx_h].double().cpu().numpy()
+    err = score_err(got_ps, ref_ps)
+    stats["prefill_score"] = err
+    assert err <= SCORE_TOL, f"prefill scores off by {err}"
+
+    # ---- both sides start from the same fp32 prompt scores
+    gpu = BuzzCache(buzz_config(wl, flags=0, max_context=N + steps, capacity=capacity))
+    if splits:
+        gpu.set_splits(splits)
+    gpu.prefill(prompt["K"], prompt["V"], init_score=ps)
+    ora = OracleCache(oracle_config(wl, U, capacity=capacity))
+    ora.prefill(Kp, Vp, init_score=got_ps[:, None, :])
+    auto = None
+    if check_auto:
+        auto = BuzzCache(buzz_config(wl, flags=FLAG_AUTO_EVICT, max_context=N + steps, capacity=capacity))
+        if splits:
+            auto.set_splits(splits)
+        q_obs = prompt["q_obs"][:, :, prompt["q_obs"].shape[2] - n_obs:, :].contiguous() if n_obs else None
+        auto.prefill(prompt["K"], prompt["V"], q_obs=q_obs)                # scoring + sampling in one call
+
+    def compare_state(tag):
+        Kg, Vg, Sg, Pg = gpu.export()
+        Ko, Vo, So, Po = ora.export()
+        assert gpu.lengths() == ora.lengths(), f"{tag}: sizes {gpu.lengths()} vs {ora.lengths()}"
+        pg = Pg[uidx_b, uidx_h].cpu().numpy()
+        assert (pg == Po[:, 0]).all(), f"{tag}: retained positions differ"
+        assert (Kg[uidx_b, uidx_h].double().cpu().numpy() == Ko[:, 0]).all(), f"{tag}: K rows differ"
+        assert (Vg[uidx_b, uidx_h].double().cpu().numpy() == Vo[:, 0]).all(), f"{tag}: V rows differ"
+        sg = Sg[uidx_b, uidx_h].double().cpu().numpy()
+        e = score_err(sg, So[:, 0])
+        stats["score"] = max(stats["score"], e)
+        assert e <= SCORE_TOL, f"{tag}: scores off by {e}"
+        return sg
+
+    compare_state("after prefill")
+    out = torch.empty(wl.batch, wl.n_q_heads, D, dtype=torch.float32, device=prompt["K"].device)
+    out_auto = torch.empty_like(out)
+    T = wl.evict_every
+    for t in range(steps):
+        q, k, v = decode["q"][t], decode["k"][t], decode["v"][t]
+        gpu.decode_step(q, k, v, out)
+        ref = ora.decode_step(unit_slices(q, units, G), unit_slices(k, units, 1), unit_slices(v, units, 1))
+        got = unit_slices(out, units, G)
+        e = rel_err(got, ref)
+        stats["out"] = max(stats["out"], e)
+        assert e <= OUT_TOL, f"step {t}: output error {e} > {OUT_TOL}"
+        assert e <= OUT_EXPECT, f"step {t}: output error {e} above what fp32 accumulation should give"
+        if auto is not None:
+            auto.decode_step(q, k, v, out_auto)
+            assert torch.equal(out, out_auto), f"step {t}: auto-evict cache diverged from the manual one"
+        if gpu.lengths()[2] >= T:
+            sg = compare_state(f"step {t} before eviction")
+            ora.set_scores(sg[:, None, :])                                 # selection runs on the GPU's fp32 scores
+            gpu.evict()
+            ora.evict()
+            compare_state(f"step {t} after eviction")
+            stats["evictions"] += 1
+    compare_state("end")
+    if auto is not None:
+        a, b = gpu.export(), auto.export()
+        assert gpu.lengths() == auto.lengths()
+        for x, y in zip(a, b):
+            assert torch.equal(x, y), "auto-evict cache differs from the manually evicted one"
+        auto.close()
+    gpu.close()
+    return stats

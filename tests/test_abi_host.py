@@ -1,0 +1,180 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared symbol,
+validates arguments before touching anything, and its integer bookkeeping (Alg. 1 sizes) matches the
+oracle's, using the dry-run flag that skips all kernel launches."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.buzz_oracle import OracleCache, OracleConfig
+from paper_2410_23079_amd import (FLAG_AUTO_EVICT, FLAG_DRY_RUN, BuzzCache, BuzzConfig, BuzzError, library_path,
+                                  load_library, workspace_bytes)
+from paper_2410_23079_amd.binding import EXPORTS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+DRY = FLAG_AUTO_EVICT | FLAG_DRY_RUN
+
+
+def cfg(**kw):
+    base = dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, kv_dtype="bf16", sink=4, window=64, segment=16,
+                keep=2, evict_every=16, max_context=4096, old_stride=1, flags=DRY)
+    base.update(kw)
+    return BuzzConfig(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "buzz.h")).read()
+    declared = set(re.findall(r"\b(buzz_[a-z_]+)\s*\(", header))
+    assert declared == set(EXPORTS)
+    lib = ctypes.CDLL(library_path())
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror_covers_all_codes():
+    lib = load_library()
+    texts = {lib.buzz_strerror(c).decode() for c in range(0, -6, -1)}
+    assert len(texts) == 6 and "unknown status" not in texts
+    assert lib.buzz_strerror(-99).decode() == "unknown status"
+
+
+@pytest.mark.parametrize("bad", [
+    dict(batch=0), dict(n_q_heads=7), dict(kv_dtype_code=5), dict(sink=-1), dict(window=-1), dict(segment=0),
+    dict(keep=-1), dict(evict_every=0), dict(old_stride=-1), dict(max_context=0), dict(capacity=10),
+    dict(flags=64), dict(softmax_scale=float("nan")), dict(softmax_scale=-1.0),
+])
+def test_invalid_configurations_are_rejected(bad):
+    c = cfg()
+    raw = c.to_c()
+    for k, v in bad.items():
+        setattr(raw, "kv_dtype" if k == "kv_dtype_code" else k, v)
+    out = ctypes.c_size_t()
+    assert load_library().buzz_workspace_bytes(ctypes.byref(raw), ctypes.byref(out)) == -1
+
+
+@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(n_q_heads=6), dict(segment=5000)])
+def test_unsupported_shapes_say_so(bad):
+    with pytest.raises(BuzzError) as e:
+        workspace_bytes(cfg(**bad))
+    assert e.value.code == -5
+
+
+def test_null_pointers_and_small_workspace():
+    lib = load_library()
+    raw = cfg(flags=FLAG_AUTO_EVICT).to_c()
+    h = ctypes.c_void_p()
+    assert lib.buzz_workspace_bytes(None, None) == -1
+    assert lib.buzz_cache_create(ctypes.byref(raw), None, 1 << 40, ctypes.byref(h)) == -1        # no workspace
+    assert lib.buzz_cache_create(ctypes.byref(raw), 0x1001, 1 << 40, ctypes.byref(h)) == -1      # misaligned
+    assert lib.buzz_cache_create(ctypes.byref(raw), 0x1000, 1024, ctypes.byref(h)) == -2         # too small
+    assert lib.buzz_cache_len(None, None, None, None) == -1
+    assert lib.buzz_decode_step(None, None, None, None, None, None) == -1
+    assert lib.buzz_cache_destroy(None) == 0
+
+
+def test_state_errors_and_argument_checks_come_before_any_launch():
+    lib = load_library()
+    raw = cfg(flags=FLAG_AUTO_EVICT).to_c()       # a real (non-dry) handle over a fake workspace: nothing may touch it
+    h = ctypes.c_void_p()
+    need = workspace_bytes(cfg(flags=FLAG_AUTO_EVICT))
+    assert lib.buzz_cache_create(ctypes.byref(raw), 0x10000, need, ctypes.byref(h)) == 0
+    assert lib.buzz_decode_step(h, 1, 1, 1, 1, None) == -3          # no prefill yet
+    assert lib.buzz_evict(h, None) == -3
+    assert lib.buzz_cache_export(h, None, None, None, None, None) == -3
+    assert lib.buzz_prefill(h, None, None, 10, None, 0, None, None) == -1        # null K, V
+    assert lib.buzz_prefill(h, 1, 1, 10, None, 3, None, None) == -1              # n_obs without q_obs
+    assert lib.buzz_prefill(h, 1, 1, 10, 1, 11, None, None) == -1                # n_obs > n_prompt
+    assert lib.buzz_prefill(h, 1, 1, 5000, None, 0, None, None) == -2            # beyond max_context
+    assert lib.buzz_cache_set_splits(h, -1) == -1
+    assert lib.buzz_cache_set_splits(h, 100000) == -1
+    assert lib.buzz_cache_destroy(h) == 0
+
+
+def test_workspace_grows_with_context_and_covers_kv():
+    small, big = workspace_bytes(cfg(max_context=2048)), workspace_bytes(cfg(max_context=65536))
+    assert big > small
+    c = cfg(max_context=65536)
+    kv_min = 2 * c.batch * c.n_kv_heads * (c.sink + c.window + c.evict_every) * c.head_dim * 2
+    assert big > kv_min
+
+
+def closed_form(N, steps, k, w, s, c, T, sh):
+    def evict(n, n_old):
+        if n <= k + w:
+            return n, n_old
+        new = n - k - n_old - w
+        o2 = -(-n_old // sh)
+        n2 = min(c, s) * (new // s) + min(c, new % s)
+        return k + o2 + n2 + w, o2 + n2
+    n, n_old = N, 0
+    if n - k - w >= T:
+        n, n_old = evict(n, n_old)
+    sizes = [(n, n_old)]
+    for _ in range(steps):
+        n += 1
+        if n - k - n_old - w >= T:
+            n, n_old = evict(n, n_old)
+        sizes.append((n, n_old))
+    return sizes
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_dry_run_sizes_match_closed_form_and_oracle(seed):
+    r = np.random.default_rng(seed)
+    k, w = int(r.integers(0, 6)), int(r.integers(0, 50))
+    s, keep = int(r.integers(1, 20)), int(r.integers(0, 5))
+    T = int(r.integers(1, 40))
+    old_stride = int(r.choice([0, 1, 2, 3]))
+    sh = old_stride or (s + 1) // 2
+    N, steps = int(r.integers(0, 400)), 150
+    g = BuzzCache(cfg(sink=k, window=w, segment=s, keep=keep, evict_every=T, old_stride=old_stride,
+                      max_context=N + steps))
+    g.prefill(None, None, n_prompt=N)
+    o = OracleCache(OracleConfig(1, 1, 1, 2, sink=k, window=w, segment=s, keep=keep, evict_every=T,
+                                 old_stride=old_stride))
+    o.prefill(np.zeros((1, 1, N, 2)), np.zeros((1, 1, N, 2)))
+    expect = closed_form(N, steps, k, w, s, keep, T, sh)
+    assert g.lengths()[:2] == expect[0] == o.lengths()[:2]
+    z = np.zeros((1, 1, 2))
+    for t in range(steps):
+        g.decode_step(None, None, None, None)
+        o.decode_step(z, z, z)
+        assert g.lengths() == o.lengths()
+        assert g.lengths()[:2] == expect[t + 1]
+    with pytest.raises(BuzzError) as e:                       # max_context reached
+        g.decode_step(None, None, None, None)
+    assert e.value.code == -2
+
+
+def test_dry_run_benchmark_configs_match_the_sizes_in_the_scope_table():
+    from workloads import WORKLOADS
+    expect = {"tiny": (96, 112), "llama7b_layer": (1412, 1476), "llama7b_full": (3844, 3876),
+              "gqa8b_layer": (7684, 7716), "long131k": (23556, 23572)}
+    for name, wl in WORKLOADS.items():
+        g = BuzzCache(BuzzConfig(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.sink, wl.window,
+                                 wl.segment, wl.keep, wl.evict_every, wl.max_context, old_stride=wl.old_stride,
+                                 flags=DRY))
+        g.prefill(None, None, n_prompt=wl.prompt)
+        a = g.lengths()[0]
+        for _ in range(wl.decode_steps):
+            g.decode_step(None, None, None, None)
+        assert (a, g.lengths()[0]) == expect[name], name
+
+
+def test_explicit_capacity_and_remark2_resampling():
+    # paper stride: prefill keeps halving the survivors until they fit the old capacity
+    g = BuzzCache(cfg(sink=4, window=64, segment=16, keep=1, evict_every=16, old_stride=0, capacity=4 + 64 + 16 + 6,
+                      max_context=2000))
+    g.prefill(None, None, n_prompt=512)
+    o = OracleCache(OracleConfig(1, 1, 1, 2, sink=4, window=64, segment=16, keep=1, evict_every=16, old_stride=0,
+                                 capacity=4 + 64 + 16 + 6))
+    o.prefill(np.zeros((1, 1, 512, 2)), np.zeros((1, 1, 512, 2)))
+    assert g.lengths() == o.lengths() and g.lengths()[1] <= 6
+    # persistent survivors cannot be resampled: the prefill must refuse
+    g2 = BuzzCache(cfg(sink=4, window=64, segment=16, keep=1, evict_every=16, old_stride=1, capacity=4 + 64 + 16 + 6,
+                       max_context=2000))
+    with pytest.raises(BuzzError) as e:
+        g2.prefill(None, None, n_prompt=512)
+    assert e.value.code == -2

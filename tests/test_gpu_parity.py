@@ -1,0 +1,178 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle in lock-step.
+
+Bars (written out in tests/lockstep.py): retained positions, K rows and V rows bit-exact; attention
+outputs within 2e-3 max relative error per head vector (and within 1e-4, what fp32 accumulation gives);
+accumulated scores within 1e-4.
+"""
+import numpy as np
+import pytest
+import torch
+
+from workloads import decode_inputs, get_workload, prompt_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def lockstep():
+    from tests import lockstep as ls
+    return ls
+
+
+def small(name="tiny", **kw):
+    return get_workload(name).scaled(**kw)
+
+
+def run(wl, device="cuda", **kw):
+    p = prompt_inputs(wl, device=device)
+    d = decode_inputs(wl, device=device)
+    print(f"[parity] {wl.name} B{wl.batch} Hq{wl.n_q_heads} Hkv{wl.n_kv_heads} D{wl.head_dim} {wl.dtype} "
+          f"N{wl.prompt} steps{wl.decode_steps} k{wl.sink} w{wl.window} s{wl.segment} c{wl.keep} "
+          f"T{wl.evict_every} sh{wl.old_stride} {kw}", flush=True)
+    st = lockstep().run_lockstep(wl, p, d, **kw)
+    print(f"[parity]   worst out {st['out']:.2e} score {st['score']:.2e} prefill-score {st['prefill_score']:.2e} "
+          f"evictions {st['evictions']}", flush=True)
+    return st
+
+
+# ------------------------------------------------------------------ config 1 in full
+def test_tiny_full():
+    st = run(get_workload("tiny"))
+    assert st["evictions"] == 256 // 16
+
+
+def test_tiny_paper_old_stride():
+    """The paper's default s^ = floor((s+1)/2): old survivors are interval-sampled at every eviction."""
+    st = run(small(old_stride=0))
+    assert st["evictions"] == 16
+
+
+def test_tiny_paper_old_stride_with_capacity():
+    """Remark 2: with an explicit capacity the prefill keeps sampling until the rows fit."""
+    wl = small(old_stride=0, prompt=512, decode_steps=40)
+    run(wl, capacity=wl.sink + wl.window + wl.evict_every + 6)
+
+
+# ------------------------------------------------------------------ shapes, dtypes, group sizes, ragged everything
+@pytest.mark.parametrize("dtype", ["fp32", "fp16", "bf16"])
+@pytest.mark.parametrize("D", [64, 128, 256])
+@pytest.mark.parametrize("G", [1, 4])
+def test_shapes(dtype, D, G):
+    wl = small(batch=2, n_kv_heads=2, n_q_heads=2 * G, head_dim=D, dtype=dtype, prompt=300, decode_steps=45,
+               sink=3, window=40, segment=7, keep=2, evict_every=10, n_obs=9)
+    run(wl)
+
+
+@pytest.mark.parametrize("G", [2, 8])
+def test_group_sizes(G):
+    wl = small(batch=1, n_kv_heads=3, n_q_heads=3 * G, head_dim=128, dtype="bf16", prompt=700, decode_steps=40,
+               sink=4, window=64, segment=16, keep=3, evict_every=16, n_obs=40)
+    run(wl)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 5, 16])
+def test_split_counts(splits):
+    wl = small(batch=1, n_kv_heads=2, n_q_heads=2, head_dim=128, dtype="fp16", prompt=2000, decode_steps=20,
+               sink=4, window=900, segment=16, keep=4, evict_every=8, n_obs=16)
+    run(wl, splits=splits, check_auto=False)
+
+
+# ------------------------------------------------------------------ degenerate cases of the method
+def test_keep_zero_streaming():
+    run(small(prompt=200, decode_steps=40, keep=0, n_obs=8))
+
+
+def test_keep_covers_segment():
+    run(small(prompt=200, decode_steps=40, segment=4, keep=4, evict_every=8, n_obs=8))
+
+
+def test_no_sink_no_window():
+    run(small(prompt=150, decode_steps=30, sink=0, window=0, segment=5, keep=1, evict_every=5, n_obs=8))
+
+
+def test_prompt_shorter_than_sink_and_window_fill():
+    """Remark 1: sink and window fill first; the first eviction happens only after T tokens left the window."""
+    run(small(prompt=2, decode_steps=120, sink=4, window=32, segment=8, keep=1, evict_every=8, n_obs=2))
+
+
+def test_empty_prompt():
+    run(small(prompt=0, decode_steps=60, sink=2, window=16, segment=4, keep=1, evict_every=4, n_obs=0))
+
+
+def test_segment_longer_than_wave():
+    run(small(prompt=1500, decode_steps=10, sink=4, window=64, segment=200, keep=5, evict_every=300, n_obs=16))
+
+
+def test_unbuffered_eviction_every_step():
+    run(small(prompt=100, decode_steps=50, sink=2, window=20, segment=3, keep=1, evict_every=1, n_obs=4))
+
+
+def test_capacity_error_when_eviction_is_skipped():
+    from paper_2410_23079_amd import BuzzCache, BuzzError
+    ls = lockstep()
+    wl = small(prompt=100, decode_steps=64, sink=2, window=20, segment=4, keep=1, evict_every=4)
+    p, d = prompt_inputs(wl, device="cuda"), decode_inputs(wl, device="cuda")
+    c = BuzzCache(ls.buzz_config(wl, flags=0))
+    c.prefill(p["K"], p["V"])
+    out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device="cuda")
+    for t in range(4):
+        c.decode_step(d["q"][t], d["k"][t], d["v"][t], out)
+    before = c.lengths()
+    with pytest.raises(BuzzError) as e:
+        c.decode_step(d["q"][4], d["k"][4], d["v"][4], out)
+    assert e.value.code == -2 and c.lengths() == before        # failed call left the cache unchanged
+    c.evict()
+    c.decode_step(d["q"][4], d["k"][4], d["v"][4], out)
+    torch.cuda.synchronize()
+
+
+def test_log_n_scale_argument():
+    """Sec. 3.5: the log-n variant only changes the softmax scale, which is a configuration argument."""
+    import math
+    ls = lockstep()
+    wl = small(prompt=300, decode_steps=20, n_obs=8)
+    p, d = prompt_inputs(wl, device="cuda"), decode_inputs(wl, device="cuda")
+    scale = math.log(812) / math.log(512) / math.sqrt(wl.head_dim)
+    from oracle.buzz_oracle import OracleCache
+    from paper_2410_23079_amd import BuzzCache
+    units = [(0, h) for h in range(wl.n_kv_heads)]
+    g = BuzzCache(ls.buzz_config(wl, softmax_scale=scale))
+    o = OracleCache(ls.oracle_config(wl, len(units), softmax_scale=scale, auto_evict=True))
+    g.prefill(p["K"], p["V"])
+    o.prefill(ls.unit_slices(p["K"], units, 1), ls.unit_slices(p["V"], units, 1))
+    out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device="cuda")
+    for t in range(3):                                           # no eviction yet: scores cannot reorder anything
+        g.decode_step(d["q"][t], d["k"][t], d["v"][t], out)
+        ref = o.decode_step(ls.unit_slices(d["q"][t], units, 1), ls.unit_slices(d["k"][t], units, 1),
+                            ls.unit_slices(d["v"][t], units, 1))
+        assert ls.rel_err(ls.unit_slices(out, units, 1), ref) <= ls.OUT_EXPECT
+
+
+# ------------------------------------------------------------------ full-size configs, sampled units
+def sampled_units(wl, count, seed):
+    r = np.random.default_rng(seed)
+    flat = r.choice(wl.batch * wl.n_kv_heads, size=min(count, wl.batch * wl.n_kv_heads), replace=False)
+    return sorted((int(u) // wl.n_kv_heads, int(u) % wl.n_kv_heads) for u in flat)
+
+
+def test_llama7b_layer_full_size():
+    wl = get_workload("llama7b_layer")
+    st = run(wl, units=sampled_units(wl, 6, 2))
+    assert st["evictions"] == 512 // 32
+
+
+def test_gqa8b_layer_full_size():
+    wl = get_workload("gqa8b_layer").scaled(decode_steps=130)
+    st = run(wl, units=sampled_units(wl, 3, 4), check_auto=False)
+    assert st["evictions"] == 2
+
+
+def test_long131k_full_size():
+    wl = get_workload("long131k").scaled(decode_steps=130)
+    st = run(wl, units=sampled_units(wl, 2, 5), check_auto=False)
+    assert st["evictions"] == 1
+
+
+def test_llama7b_full_one_layer_full_size():
+    wl = get_workload("llama7b_full").scaled(decode_steps=66)
+    st = run(wl, units=sampled_units(wl, 3, 3), check_auto=False)
+    assert st["evictions"] == 1

@@ -316,7 +316,7 @@ def closed_form_sizes(N, steps, k, w, s, c, T, sh):
             return n, n_old
         new = n - k - n_old - w
         old2 = -(-n_old // sh)
-        new2 = c * (new // s) + min(c, new % s)
+        new2 = min(c, s) * (new // s) + min(c, new % s)
         return k + old2 + new2 + w, old2 + new2
     n, n_old = N, 0
     if n - k - w >= T:
