@@ -72,14 +72,12 @@ def cpu_baseline(wl, budget_s=20.0):
     import numpy as np
     from oracle.buzz_oracle import OracleCache, OracleConfig, _load
     from workloads import decode_inputs, prompt_inputs
-    max_units = 64                                     # bound host memory: units are independent and identical in cost
-    B = wl.batch
-    Hkv = wl.n_kv_heads
-    while B * Hkv > max_units and B > 1:
-        B //= 2
+    B = wl.batch                                       # bound host memory (fp64 copies of the prompt) to ~4 GB:
+    while B > 1 and B * wl.n_kv_heads * wl.prompt * wl.head_dim * 16 > (4 << 30):
+        B //= 2                                        # units are independent and identical in cost
     sub = wl.scaled(batch=B)
     p = prompt_inputs(sub, device="cpu")
-    steps = min(sub.decode_steps, 4 * sub.evict_every)
+    steps = sub.decode_steps
     d = decode_inputs(sub, device="cpu", steps=steps)
     o = OracleCache(OracleConfig(sub.batch, sub.n_q_heads, sub.n_kv_heads, sub.head_dim, sub.sink, sub.window,
                                  sub.segment, sub.keep, sub.evict_every, sub.old_stride))

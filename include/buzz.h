@@ -50,7 +50,12 @@ enum { BUZZ_FP32 = 0, BUZZ_FP16 = 1, BUZZ_BF16 = 2 };
 
 enum {
     BUZZ_FLAG_AUTO_EVICT = 1u, /* buzz_decode_step evicts by itself when T new tokens are buffered */
-    BUZZ_FLAG_DRY_RUN = 2u     /* do all host bookkeeping and validation but launch nothing (no GPU needed) */
+    BUZZ_FLAG_DRY_RUN = 2u,    /* do all host bookkeeping and validation but launch nothing (no GPU needed) */
+    /* How the decode kernel reads K and V.  Default (neither flag): streaming loads when one step of this
+       cache reads more than the GPU's 256 MB last-level cache, cached loads otherwise.  A caller that runs many
+       layers (so that nothing survives in cache between two steps of one layer) should set STREAMING. */
+    BUZZ_FLAG_STREAMING = 4u,
+    BUZZ_FLAG_CACHED = 8u
 };
 
 /* Symbols follow the paper's notation table (Sec. 3.3). */
@@ -168,8 +173,9 @@ int buzz_cache_set_splits(buzz_cache_t* cache, int32_t n_splits);
 /*
  * Benchmark aid: per-kernel device time measured with HIP events recorded on
  * the stream each kernel is launched on.  buzz_cache_profile(cache, 1) clears
- * the counters and starts recording (two events around every launch, which
- * costs a little: use a separate pass for end-to-end timing);
+ * the counters and starts recording (every launch then carries a start and a
+ * stop event that take the kernel's own begin / end timestamps; use a separate
+ * pass for end-to-end timing);
  * buzz_cache_profile(cache, 0) stops.  buzz_cache_profile_read waits for the
  * recorded events, then fills `out` (host pointer).
  * Errors: BUZZ_EINVAL, BUZZ_EHIP.

@@ -11,10 +11,13 @@ import os
 from dataclasses import dataclass
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libbuzz.so")
+# BUZZ_LIBRARY points at a differently built copy of the same library (tuning sweeps); default: the in-tree build
+_LIB_PATH = os.environ.get("BUZZ_LIBRARY") or os.path.join(_HERE, "libbuzz.so")
 
 FLAG_AUTO_EVICT = 1
 FLAG_DRY_RUN = 2
+FLAG_STREAMING = 4
+FLAG_CACHED = 8
 DTYPE_CODES = {"fp32": 0, "fp16": 1, "bf16": 2}
 
 EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step", "buzz_evict",

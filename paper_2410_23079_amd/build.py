@@ -11,20 +11,23 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbuzz.so")
 SOURCES = ["buzz_api.cpp", "attn_kernels.hip", "evict_kernels.hip", "prefill_kernels.hip"]
 FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fgpu-rdc" if False else "-fno-gpu-rdc",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU forms are switched off for the whole library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every source and link the shared library; always recompiles."""
+def build(verbose: bool = False, extra_flags=(), out_path: str = LIB, obj_dir: str = CSRC) -> str:
+    """Compile every source and link the shared library; always recompiles.
+
+    ``extra_flags`` / ``out_path`` / ``obj_dir`` let a tuning sweep build differently configured copies elsewhere."""
     objs = []
     procs = []
+    os.makedirs(obj_dir, exist_ok=True)
     for src in SOURCES:
-        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = ["hipcc", "-x", "hip", *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        cmd = ["hipcc", "-x", "hip", *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
                "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -40,9 +43,9 @@ def build(verbose: bool = False) -> str:
         failed |= p.returncode != 0
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out_path, *objs]
     subprocess.run(cmd, check=True)
-    return LIB
+    return out_path
 
 
 if __name__ == "__main__":

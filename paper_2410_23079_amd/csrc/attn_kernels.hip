@@ -1,13 +1,18 @@
-// Decode attention over the retained BUZZ cache, split over key ranges (eq. 3 / eq. 5 of the paper),
-// with the append of eq. 2 fused in, followed by the combine + accumulated-score epilogue.
+// Decode attention over the retained BUZZ cache (eq. 3 / eq. 5 of the paper) as ONE kernel per step:
+// the append of eq. 2, the split-softmax attention, the merge of the splits and the accumulated-score
+// update ("A" of Alg. 2) all happen inside attn_split.
 //
-// Kernel 1 (attn_split): one block per (key-range split, unit).  A wave reads 64 x 16 B per load
-// instruction = RPW consecutive cache rows, LPR = 64 / RPW lanes per row, so every load is one
-// contiguous 1 KB burst.  A row's q.k dot product is an LPR-lane DPP reduction; softmax runs online
-// per lane group; p.V accumulates in registers.  The scaled logit of every row goes to a scratch
-// array so that the epilogue can turn it into a globally normalised probability.
-// Kernel 2 (combine_score): merges the split partials into the output and adds
-// sum_g softmax(...)_row to every retained row's accumulated score ("A" of Alg. 2).
+//  - One block per (key-range split, unit).  A wave reads 64 x 16 B per load instruction = RPW
+//    consecutive cache rows, LPR = 64 / RPW lanes per row: every load is one contiguous 1 KB burst.
+//    q.k is a two-element-dot chain per lane plus an LPR-lane DPP reduction; softmax runs online per
+//    lane group; p.V accumulates in registers.
+//  - The scaled logit of every row is written to a scratch array.  A row's probability needs the
+//    maximum and sum over ALL splits, which only exist once the step is over, so the score update of
+//    step t is applied by step t+1 while it streams the same rows anyway (one lane per row, coalesced):
+//    score += sum_g exp2(logit_t - M_t[g]) / L_t[g].  flush_scores applies a pending update right away;
+//    the host calls it before anything reads the scores (eviction, export).
+//  - The block that finishes last for a unit (atomic ticket, nobody waits) merges the split partials
+//    into the attention output and publishes (M, 1/L) for the next step's score update.
 #include "buzz_internal.h"
 
 namespace buzz {
@@ -17,38 +22,88 @@ struct bf16_t { uint16_t x; };
 struct fp16_t { uint16_t x; };
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// Build-time tuning knobs (defaults are the measured best; a sweep overrides them with -D).
+#ifndef BUZZ_U_G1
+#define BUZZ_U_G1 8      // 16-byte loads of K (and of V) in flight per lane and trip, group size 1
+#endif
+#ifndef BUZZ_U_G2
+#define BUZZ_U_G2 4
+#endif
+#ifndef BUZZ_U_G4
+#define BUZZ_U_G4 4
+#endif
+#ifndef BUZZ_U_G8
+#define BUZZ_U_G8 2
+#endif
+#ifndef BUZZ_PREFETCH
+#define BUZZ_PREFETCH 0  // 1: issue the next trip's loads before computing the current one
+#endif
+#ifndef BUZZ_MIN_BLOCKS
+#define BUZZ_MIN_BLOCKS 1  // second argument of __launch_bounds__
+#endif
 
 template <typename T> struct Elem;
+// cvt: 16 bytes -> VEC floats.  dot: sum over the 16 bytes of q * k in fp32 (16-bit types use the
+// two-element dot instruction on the raw words: exact products, fp32 accumulation, no conversion).
 template <> struct Elem<float> {
     static constexpr int VEC = 4;
-    static __device__ inline void cvt(const uint4& r, float* f) {
+    static __device__ inline void cvt(const u32x4& r, float* f) {
         f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
         f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+    }
+    static __device__ inline float dot(const u32x4& q, const u32x4& k) {
+        float d = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) d = fmaf(__uint_as_float(q[i]), __uint_as_float(k[i]), d);
+        return d;
     }
 };
 template <> struct Elem<bf16_t> {
     static constexpr int VEC = 8;
-    static __device__ inline void cvt(const uint4& r, float* f) {
-        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+    static __device__ inline void cvt(const u32x4& r, float* f) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            f[2 * i] = __uint_as_float(w[i] << 16);
-            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            f[2 * i] = __uint_as_float(r[i] << 16);
+            f[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
         }
+    }
+    static __device__ inline float dot(const u32x4& q, const u32x4& k) {
+        float d = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, (unsigned int)q[i]),
+                                                __builtin_bit_cast(bf16x2_t, (unsigned int)k[i]), d, false);
+        return d;
     }
 };
 template <> struct Elem<fp16_t> {
     static constexpr int VEC = 8;
-    static __device__ inline void cvt(const uint4& r, float* f) {
-        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+    static __device__ inline void cvt(const u32x4& r, float* f) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+            const half2_t h = __builtin_bit_cast(half2_t, (unsigned int)r[i]);
             f[2 * i] = (float)h.x;
             f[2 * i + 1] = (float)h.y;
         }
     }
+    static __device__ inline float dot(const u32x4& q, const u32x4& k) {
+        float d = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            d = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, (unsigned int)q[i]),
+                                       __builtin_bit_cast(half2_t, (unsigned int)k[i]), d, false);
+        return d;
+    }
 };
+
+// NT: streaming hint for data that will not be re-read before it would be evicted anyway
+template <bool NT> __device__ inline u32x4 load16(const char* p) {
+    if constexpr (NT) return __builtin_nontemporal_load((const u32x4*)p);
+    else return *(const u32x4*)p;
+}
 
 template <int CTRL> __device__ inline float dpp_move(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
@@ -67,8 +122,11 @@ template <int LPR> __device__ inline float row_sum(float v) {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <typename T, int D, int G, int U>
-__global__ __launch_bounds__(256) void attn_split_kernel(const AttnArgs a)
+// A split's logical row range is cut into at most four physically contiguous runs (linear region,
+// ring before the wrap, ring after the wrap, the row being appended), so the streaming loop only
+// advances pointers.  Within a run the block's four waves take tiles of WROWS rows round-robin.
+template <typename T, int D, int G, int U, bool NT>
+__global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const AttnArgs a)
 {
     using E = Elem<T>;
     constexpr int VEC = E::VEC;
@@ -79,32 +137,40 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnArgs a)
     constexpr int WROWS = RPW * U;        // rows one wave consumes per trip
     constexpr int TILE = NW * WROWS;
     static_assert(LPR >= 8 && LPR <= 64, "row must span 8..64 lanes");
+    static_assert(WROWS <= 64, "one lane per row when the logits are written out");
+
+    __shared__ float sm_logit[NW][G][WROWS];
+    __shared__ float sm_m[NW][G], sm_l[NW][G];
+    __shared__ float sm_acc[NW][G][D];
+    __shared__ float sm_w[kMaxSplits][G], sm_pl[kMaxSplits][G];
+    __shared__ float sm_M[G], sm_invL[G];
+    __shared__ int sm_ticket;
 
     const int split = blockIdx.x, unit = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane % LPR, rs = lane / LPR;
     const int b = unit / a.Hkv, kvh = unit - b * a.Hkv;
 
-    float qf[G][VEC];
+    u32x4 qr[G];                                          // this lane's 16 bytes of every query head, raw
     {
         const char* qb = (const char*)a.q + (size_t)(b * a.Hq + kvh * G) * ROWB + c * 16;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const uint4 r = *(const uint4*)(qb + (size_t)g * ROWB);
-            E::cvt(r, qf[g]);
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) qf[g][v] *= a.scale_log2;
-        }
+        for (int g = 0; g < G; ++g) qr[g] = *(const u32x4*)(qb + (size_t)g * ROWB);
     }
 
-    const int j0 = split * a.rows_per_split;
-    const int j1 = min(a.n, j0 + a.rows_per_split);
-    const int jn = a.n - 1;
     const size_t ubase = (size_t)unit * a.cap;
-    char* Kb = (char*)a.K + ubase * ROWB + c * 16;
-    char* Vb = (char*)a.V + ubase * ROWB + c * 16;
-    const char* knew = (const char*)a.k_new + (size_t)unit * ROWB + c * 16;
-    const char* vnew = (const char*)a.v_new + (size_t)unit * ROWB + c * 16;
+    char* Kb = (char*)a.K + ubase * ROWB;                 // wave-uniform bases; lanes add 32-bit offsets
+    char* Vb = (char*)a.V + ubase * ROWB;
+    const unsigned lane_off = c * 16;
+    float* logit_u = a.logit + ubase * G;                 // [G][cap] for this unit, written by this step
+    const float* logit_prev_u = a.logit_prev + ubase * G;  // the previous step's logits
+    float* score_u = a.score + ubase;
+    float Mp[G], iLp[G];                                   // previous step's global max and 1/sum per head
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        Mp[g] = a.pending ? a.stat_prev[((size_t)unit * G + g) * 2] : 0.f;
+        iLp[g] = a.pending ? a.stat_prev[((size_t)unit * G + g) * 2 + 1] : 0.f;
+    }
 
     float m[G], l[G], acc[G][VEC];
 #pragma unroll
@@ -114,58 +180,46 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnArgs a)
         for (int v = 0; v < VEC; ++v) acc[g][v] = 0.f;
     }
 
-    for (int base = j0 + wave * WROWS; base < j1; base += TILE) {
-        uint4 kr[U], vr[U];
-        int ph[U];
-        bool ok[U];
+    // rows of the run that this lane loads in the trip starting at `base`; masked lanes re-read the run's last row
+    auto load_tile = [&](u32x4 (&kr)[U], u32x4 (&vr)[U], const char* kp, const char* vp, int base, int cnt) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int j = base + u * RPW + rs;
-            ok[u] = j < j1;
-            const int jj = ok[u] ? j : j0;              // masked lanes re-read a valid row
-            ph[u] = a.map.phys(jj);
-            const bool is_new = jj == jn;
-            const char* kp = is_new ? knew : Kb + (size_t)ph[u] * ROWB;
-            const char* vp = is_new ? vnew : Vb + (size_t)ph[u] * ROWB;
-            kr[u] = *(const uint4*)kp;
-            vr[u] = *(const uint4*)vp;
-            if (is_new && ok[u]) {                      // eq. 2: the new row joins the cache
-                *(uint4*)(Kb + (size_t)a.new_phys * ROWB) = kr[u];
-                *(uint4*)(Vb + (size_t)a.new_phys * ROWB) = vr[u];
-                if (c == 0) a.pos[ubase + a.new_phys] = a.new_pos;
-            }
+            const unsigned off = (unsigned)min(base + u * RPW + rs, cnt - 1) * ROWB + lane_off;
+            kr[u] = load16<NT>(kp + off);
+            vr[u] = load16<NT>(vp + off);
         }
+    };
+
+    auto compute_tile = [&](const u32x4 (&kr)[U], const u32x4 (&vr)[U], int base, int cnt, int phys0, bool fresh) {
         float s[G][U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float kf[VEC];
-            E::cvt(kr[u], kf);
+            const bool ok = base + u * RPW + rs < cnt;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                float d = 0.f;
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) d = fmaf(qf[g][v], kf[v], d);
-                d = row_sum<LPR>(d);
-                s[g][u] = ok[u] ? d : -INFINITY;
-            }
-            if (ok[u] && c == 0) {
-                float* lp = a.logit + (ubase + ph[u]) * G;
-                if constexpr (G == 4) {
-                    *(float4*)lp = make_float4(s[0][u], s[1][u], s[2][u], s[3][u]);
-                } else if constexpr (G == 2) {
-                    *(float2*)lp = make_float2(s[0][u], s[1][u]);
-                } else if constexpr (G == 8) {
-                    *(float4*)lp = make_float4(s[0][u], s[1][u], s[2][u], s[3][u]);
-                    *(float4*)(lp + 4) = make_float4(s[4][u], s[5][u], s[6][u], s[7][u]);
-                } else {
-#pragma unroll
-                    for (int g = 0; g < G; ++g) lp[g] = s[g][u];
-                }
+                const float d = row_sum<LPR>(E::dot(qr[g], kr[u])) * a.scale_log2;
+                s[g][u] = ok ? d : -INFINITY;
+                if (c == 0) sm_logit[wave][g][u * RPW + rs] = d;
             }
         }
-        float vf[U][VEC];
+        // one lane per row (LDS ops of a wave complete in order): coalesced store of the trip's logits and
+        // the previous step's pending score update; a freshly appended row starts from score 0
+        __builtin_amdgcn_wave_barrier();
+        if (lane < WROWS && base + lane < cnt) {
+            const int ph = phys0 + base + lane;
 #pragma unroll
-        for (int u = 0; u < U; ++u) E::cvt(vr[u], vf[u]);
+            for (int g = 0; g < G; ++g) logit_u[(size_t)g * a.cap + ph] = sm_logit[wave][g][lane];
+            if (fresh) {
+                score_u[ph] = 0.f;
+            } else if (a.pending) {
+                float sc = score_u[ph];
+#pragma unroll
+                for (int g = 0; g < G; ++g) sc += fast_exp2(logit_prev_u[(size_t)g * a.cap + ph] - Mp[g]) * iLp[g];
+                score_u[ph] = sc;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        // online softmax: s becomes the unnormalised probability relative to the running maximum
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             float tmax = s[g][0];
@@ -177,16 +231,74 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnArgs a)
             m[g] = mn;
             float psum = 0.f;
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[g][v] *= alpha;
-#pragma unroll
             for (int u = 0; u < U; ++u) {
-                const float p = fast_exp2(s[g][u] - mref);
-                psum += p;
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) acc[g][v] = fmaf(p, vf[u][v], acc[g][v]);
+                s[g][u] = fast_exp2(s[g][u] - mref);
+                psum += s[g][u];
             }
             l[g] = fmaf(l[g], alpha, psum);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[g][v] *= alpha;
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float vf[VEC];
+            E::cvt(vr[u], vf);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[g][v] = fmaf(s[g][u], vf[v], acc[g][v]);
+            }
+        }
+    };
+
+    const int j0 = split * a.rows_per_split;
+    const int j1 = min(a.n, j0 + a.rows_per_split);
+    const int jl1 = min(j1, a.n - 1);                     // rows already stored in the arena end here
+    const int wrap = a.map.front + a.map.ring_cap - a.map.ring_head;   // first logical row after the ring wraps
+
+    for (int run = 0; run < 4; ++run) {
+        int lo, hi, phys0;
+        const char *kp, *vp;
+        if (run == 0) { lo = j0; hi = min(jl1, a.map.front); phys0 = lo; }
+        else if (run == 1) { lo = max(j0, a.map.front); hi = min(jl1, wrap); phys0 = a.map.ring_base + a.map.ring_head + (lo - a.map.front); }
+        else if (run == 2) { lo = max(j0, wrap); hi = jl1; phys0 = a.map.ring_base + (lo - wrap); }
+        else { lo = a.n - 1; hi = j1 == a.n ? a.n : lo; phys0 = a.new_phys; }
+        const int cnt = hi - lo;
+        if (cnt <= 0) continue;
+        if (run < 3) {
+            kp = Kb + (size_t)phys0 * ROWB;
+            vp = Vb + (size_t)phys0 * ROWB;
+        } else {                                          // eq. 2: the new row comes from the caller and joins the cache
+            kp = (const char*)a.k_new + (size_t)unit * ROWB;
+            vp = (const char*)a.v_new + (size_t)unit * ROWB;
+            if (wave == 0 && rs == 0) {
+                *(u32x4*)(Kb + (size_t)a.new_phys * ROWB + lane_off) = *(const u32x4*)(kp + lane_off);
+                *(u32x4*)(Vb + (size_t)a.new_phys * ROWB + lane_off) = *(const u32x4*)(vp + lane_off);
+                if (c == 0) a.pos[ubase + a.new_phys] = a.new_pos;
+            }
+        }
+#if BUZZ_PREFETCH
+        u32x4 ka[U], va[U], kb[U], vb[U];
+        int base = wave * WROWS;
+        if (base < cnt) load_tile(ka, va, kp, vp, base, cnt);
+        while (base < cnt) {
+            int nb = base + TILE;
+            if (nb < cnt) load_tile(kb, vb, kp, vp, nb, cnt);
+            compute_tile(ka, va, base, cnt, phys0, run == 3);
+            base = nb;
+            if (base >= cnt) break;
+            nb = base + TILE;
+            if (nb < cnt) load_tile(ka, va, kp, vp, nb, cnt);
+            compute_tile(kb, vb, base, cnt, phys0, run == 3);
+            base = nb;
+        }
+#else
+        for (int base = wave * WROWS; base < cnt; base += TILE) {
+            u32x4 kr[U], vr[U];
+            load_tile(kr, vr, kp, vp, base, cnt);
+            compute_tile(kr, vr, base, cnt, phys0, run == 3);
+        }
+#endif
     }
 
     // merge the RPW lane groups of this wave (same columns, different rows)
@@ -210,8 +322,6 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnArgs a)
     }
 
     // merge the waves of the block through LDS and emit this split's partial
-    __shared__ float sm_m[NW][G], sm_l[NW][G];
-    __shared__ float sm_acc[NW][G][D];
     if (rs == 0) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -244,87 +354,111 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const AttnArgs a)
             a.part_ml[(pbase + g) * 2 + 1] = L;
         }
     }
+
+    // ticket: the block that arrives last for this unit sees every split's partial and merges them
+    const int S = a.n_splits;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __syncthreads();
+    if (tid == 0) sm_ticket = atomicAdd(a.ticket + unit, 1);
+    __syncthreads();
+    if (sm_ticket != S - 1) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (tid == 0) a.ticket[unit] = 0;                     // ready for the next step
+    const float* ml = a.part_ml + (size_t)unit * a.s_cap * G * 2;
+    for (int i = tid; i < S * G; i += 256) {
+        sm_w[i / G][i % G] = ml[i * 2];
+        sm_pl[i / G][i % G] = ml[i * 2 + 1];
+    }
+    __syncthreads();
+    if (tid < G) {
+        float M = -INFINITY;
+        for (int sp = 0; sp < S; ++sp) M = fmaxf(M, sm_w[sp][tid]);
+        float L = 0.f;
+        for (int sp = 0; sp < S; ++sp) {
+            const float w = fast_exp2(sm_w[sp][tid] - M);  // M is finite: the appended row is always present
+            sm_w[sp][tid] = w;
+            L = fmaf(sm_pl[sp][tid], w, L);
+        }
+        sm_M[tid] = M;
+        sm_invL[tid] = 1.0f / L;
+        a.stat[((size_t)unit * G + tid) * 2] = M;
+        a.stat[((size_t)unit * G + tid) * 2 + 1] = 1.0f / L;
+    }
+    __syncthreads();
+    const float* po = a.part_o + (size_t)unit * a.s_cap * G * D;
+    float* outp = a.out + (size_t)(b * a.Hq + kvh * G) * D;
+    for (int i = tid; i < G * D; i += 256) {
+        const int g = i / D, d = i - g * D;
+        float o = 0.f;
+        int sp = 0;
+        for (; sp + 8 <= S; sp += 8) {                    // eight independent loads in flight
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = po[((size_t)(sp + e) * G + g) * D + d];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o = fmaf(sm_w[sp + e][g], x[e], o);
+        }
+        for (; sp < S; ++sp) o = fmaf(sm_w[sp][g], po[((size_t)sp * G + g) * D + d], o);
+        outp[(size_t)g * D + d] = o * sm_invL[g];
+    }
 }
 
 constexpr int kScoreRowsPerBlock = 2048;
 
+// Applies the pending score update of the last decode step to every retained row right away.
 template <int G>
-__global__ __launch_bounds__(256) void combine_score_kernel(const AttnArgs a, const int D)
+__global__ __launch_bounds__(256) void flush_scores_kernel(const AttnArgs a)
 {
-    __shared__ float sM[G], sInvL[G];
-    __shared__ float sW[kMaxSplits][G];
     const int chunk = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
-    const int S = a.n_splits;
-    const float* ml = a.part_ml + (size_t)unit * a.s_cap * G * 2;
-    if (tid < G) {
-        float M = -INFINITY;
-        for (int s = 0; s < S; ++s) M = fmaxf(M, ml[(s * G + tid) * 2]);
-        float L = 0.f;
-        for (int s = 0; s < S; ++s) {
-            const float ms = ml[(s * G + tid) * 2];
-            const float w = fast_exp2(ms - M);          // M is finite: the appended row is always present
-            sW[s][tid] = w;
-            L = fmaf(ml[(s * G + tid) * 2 + 1], w, L);
-        }
-        sM[tid] = M;
-        sInvL[tid] = 1.0f / L;
+    float M[G], iL[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        M[g] = a.stat_prev[((size_t)unit * G + g) * 2];
+        iL[g] = a.stat_prev[((size_t)unit * G + g) * 2 + 1];
     }
-    __syncthreads();
-
     const size_t ubase = (size_t)unit * a.cap;
+    const float* logit_u = a.logit_prev + ubase * G;
     const int jbeg = chunk * kScoreRowsPerBlock;
     const int jend = min(a.n, jbeg + kScoreRowsPerBlock);
     for (int j = jbeg + tid; j < jend; j += 256) {
-        const size_t idx = ubase + a.map.phys(j);
-        float p = 0.f;
+        const int ph = a.map.phys(j);
+        float sc = a.score[ubase + ph];
 #pragma unroll
-        for (int g = 0; g < G; ++g) p += fast_exp2(a.logit[idx * G + g] - sM[g]) * sInvL[g];
-        const float old = (j == a.n - 1) ? 0.f : a.score[idx];   // the appended row starts from zero
-        a.score[idx] = old + p;
-    }
-
-    if (chunk == 0) {
-        const int b = unit / a.Hkv, kvh = unit - b * a.Hkv;
-        const float* po = a.part_o + (size_t)unit * a.s_cap * G * D;
-        float* outp = a.out + (size_t)(b * a.Hq + kvh * G) * D;
-        for (int i = tid; i < G * D; i += 256) {
-            const int g = i / D, d = i - g * D;
-            float o = 0.f;
-            for (int s = 0; s < S; ++s) o = fmaf(sW[s][g], po[((size_t)s * G + g) * D + d], o);
-            outp[(size_t)g * D + d] = o * sInvL[g];
-        }
+        for (int g = 0; g < G; ++g) sc += fast_exp2(logit_u[(size_t)g * a.cap + ph] - M[g]) * iL[g];
+        a.score[ubase + ph] = sc;
     }
 }
 
-template <int G> constexpr int unroll_for() { return G == 1 ? 8 : (G <= 4 ? 4 : 2); }
+template <int G> constexpr int unroll_for() { return G == 1 ? BUZZ_U_G1 : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8)); }
 
 template <typename T, int D, int G>
-hipError_t launch_split_t(const AttnArgs& a, int units, hipStream_t st)
+hipError_t launch_split_t(const AttnArgs& a, int units, hipStream_t st, Timing tm)
 {
     dim3 grid(a.n_splits, units), block(256);
-    hipLaunchKernelGGL((attn_split_kernel<T, D, G, unroll_for<G>()>), grid, block, 0, st, a);
+    if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, unroll_for<G>(), true>), grid, block, 0, st, tm, a);
+    else BUZZ_LAUNCH((attn_split_kernel<T, D, G, unroll_for<G>(), false>), grid, block, 0, st, tm, a);
     return hipGetLastError();
 }
 
 template <typename T, int D>
-hipError_t launch_split_g(int G, const AttnArgs& a, int units, hipStream_t st)
+hipError_t launch_split_g(int G, const AttnArgs& a, int units, hipStream_t st, Timing tm)
 {
     switch (G) {
-        case 1: return launch_split_t<T, D, 1>(a, units, st);
-        case 2: return launch_split_t<T, D, 2>(a, units, st);
-        case 4: return launch_split_t<T, D, 4>(a, units, st);
-        case 8: return launch_split_t<T, D, 8>(a, units, st);
+        case 1: return launch_split_t<T, D, 1>(a, units, st, tm);
+        case 2: return launch_split_t<T, D, 2>(a, units, st, tm);
+        case 4: return launch_split_t<T, D, 4>(a, units, st, tm);
+        case 8: return launch_split_t<T, D, 8>(a, units, st, tm);
     }
     return hipErrorInvalidValue;
 }
 
 template <typename T>
-hipError_t launch_split_d(int D, int G, const AttnArgs& a, int units, hipStream_t st)
+hipError_t launch_split_d(int D, int G, const AttnArgs& a, int units, hipStream_t st, Timing tm)
 {
     switch (D) {
-        case 64: return launch_split_g<T, 64>(G, a, units, st);
-        case 128: return launch_split_g<T, 128>(G, a, units, st);
-        case 256: return launch_split_g<T, 256>(G, a, units, st);
+        case 64: return launch_split_g<T, 64>(G, a, units, st, tm);
+        case 128: return launch_split_g<T, 128>(G, a, units, st, tm);
+        case 256: return launch_split_g<T, 256>(G, a, units, st, tm);
     }
     return hipErrorInvalidValue;
 }
@@ -342,28 +476,29 @@ int attn_tile_rows(int dtype, int D, int G)
 {
     const int vec = dtype == BUZZ_FP32 ? 4 : 8;
     const int rpw = 64 / (D / vec);
-    const int u = G == 1 ? 8 : (G <= 4 ? 4 : 2);
+    const int u = G == 1 ? BUZZ_U_G1 : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
     return 4 * rpw * u;
 }
 
-hipError_t launch_attn_split(int dtype, int D, int G, const AttnArgs& a, int units, hipStream_t st)
+hipError_t launch_attn_split(int dtype, int D, int G, const AttnArgs& a, int units, hipStream_t st, Timing tm)
 {
     switch (dtype) {
-        case BUZZ_FP32: return launch_split_d<float>(D, G, a, units, st);
-        case BUZZ_FP16: return launch_split_d<fp16_t>(D, G, a, units, st);
-        case BUZZ_BF16: return launch_split_d<bf16_t>(D, G, a, units, st);
+        case BUZZ_FP32: return launch_split_d<float>(D, G, a, units, st, tm);
+        case BUZZ_FP16: return launch_split_d<fp16_t>(D, G, a, units, st, tm);
+        case BUZZ_BF16: return launch_split_d<bf16_t>(D, G, a, units, st, tm);
     }
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_combine_score(int D, int G, const AttnArgs& a, int units, hipStream_t st)
+hipError_t launch_flush_scores(int G, const AttnArgs& a, int units, hipStream_t st, Timing tm)
 {
+    if (a.n <= 0) return hipSuccess;
     dim3 grid((a.n + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, units), block(256);
     switch (G) {
-        case 1: hipLaunchKernelGGL((combine_score_kernel<1>), grid, block, 0, st, a, D); break;
-        case 2: hipLaunchKernelGGL((combine_score_kernel<2>), grid, block, 0, st, a, D); break;
-        case 4: hipLaunchKernelGGL((combine_score_kernel<4>), grid, block, 0, st, a, D); break;
-        case 8: hipLaunchKernelGGL((combine_score_kernel<8>), grid, block, 0, st, a, D); break;
+        case 1: BUZZ_LAUNCH((flush_scores_kernel<1>), grid, block, 0, st, tm, a); break;
+        case 2: BUZZ_LAUNCH((flush_scores_kernel<2>), grid, block, 0, st, tm, a); break;
+        case 4: BUZZ_LAUNCH((flush_scores_kernel<4>), grid, block, 0, st, tm, a); break;
+        case 8: BUZZ_LAUNCH((flush_scores_kernel<8>), grid, block, 0, st, tm, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

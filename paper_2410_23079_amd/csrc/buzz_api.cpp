@@ -17,7 +17,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 struct Layout {
-    size_t K, V, score, pos, logit, part_ml, part_o, sel, stK, stV, stScore, stPos, pscore, obs_stats, total;
+    size_t K, V, score, pos, logit[2], stat[2], ticket, part_ml, part_o, sel, stK, stV, stScore, stPos, pscore, obs_stats, total;
     int32_t cap, old_cap, ring_cap, ring_base, s_cap, sel_stride, st_rows;
     int32_t units, G, elem, row_bytes, old_stride, keep;
 };
@@ -30,7 +30,9 @@ int make_layout(const buzz_config_t* c, Layout* L)
     if (c->kv_dtype < BUZZ_FP32 || c->kv_dtype > BUZZ_BF16) return BUZZ_EINVAL;
     if (c->sink < 0 || c->window < 0 || c->segment < 1 || c->keep < 0 || c->evict_every < 1) return BUZZ_EINVAL;
     if (c->old_stride < 0 || c->max_context < 1 || c->capacity < 0 || c->reserved != 0) return BUZZ_EINVAL;
-    if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN)) return BUZZ_EINVAL;
+    if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN | BUZZ_FLAG_STREAMING | BUZZ_FLAG_CACHED))
+        return BUZZ_EINVAL;
+    if ((c->flags & BUZZ_FLAG_STREAMING) && (c->flags & BUZZ_FLAG_CACHED)) return BUZZ_EINVAL;
     if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BUZZ_EINVAL;
     const int G = c->n_q_heads / c->n_kv_heads;
     if (!attn_supported(c->kv_dtype, c->head_dim, G)) return BUZZ_EUNSUPPORTED;
@@ -79,7 +81,11 @@ int make_layout(const buzz_config_t* c, Layout* L)
     L->V = take(rows * L->row_bytes);
     L->score = take(rows * 4);
     L->pos = take(rows * 4);
-    L->logit = take(rows * G * 4);
+    L->logit[0] = take(rows * G * 4);
+    L->logit[1] = take(rows * G * 4);
+    L->stat[0] = take((size_t)units * G * 2 * 4);
+    L->stat[1] = take((size_t)units * G * 2 * 4);
+    L->ticket = take((size_t)units * 4);
     L->part_ml = take((size_t)units * s_cap * G * 2 * 4);
     L->part_o = take((size_t)units * s_cap * G * c->head_dim * 4);
     L->sel = take((size_t)units * L->sel_stride * 4);
@@ -107,10 +113,14 @@ struct buzz_cache {
     bool ready;
     int64_t sink_filled, n_old, tail, head, tokens_seen;
     int32_t user_splits;
+    // the score update of the last decode step is applied lazily (by the next step or by a flush)
+    bool pending;
+    int last_buf;   // logit / stat buffer the last decode step wrote
     // benchmark profiling: event pairs per kernel class (0 attn, 1 epilogue, 2 eviction)
     bool prof;
     std::vector<hipEvent_t> ev[3];
     double prof_row_bytes;
+    int64_t prof_evictions;
 
     int64_t n() const { return sink_filled + n_old + tail; }
     int64_t new_count() const
@@ -136,14 +146,18 @@ inline bool alive(const buzz_cache_t* c) { return c && c->magic == kMagic; }
 
 constexpr size_t kMaxProfEvents = 1 << 15;
 
-// records an event on `st` for kernel class `cls` while profiling is on
-inline void prof_mark(buzz_cache_t* c, int cls, hipStream_t st)
+// a fresh event pair for one launch of kernel class `cls` while profiling is on, else an empty Timing
+inline Timing prof_pair(buzz_cache_t* c, int cls)
 {
-    if (!c->prof || c->ev[cls].size() >= kMaxProfEvents) return;
-    hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return;
-    if (hipEventRecord(e, st) != hipSuccess) { (void)hipEventDestroy(e); return; }
-    c->ev[cls].push_back(e);
+    Timing tm;
+    if (!c->prof || c->ev[cls].size() >= kMaxProfEvents) return tm;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return tm;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return tm; }
+    c->ev[cls].push_back(a);
+    c->ev[cls].push_back(b);
+    tm.begin = a; tm.end = b;
+    return tm;
 }
 
 void prof_clear(buzz_cache_t* c)
@@ -153,6 +167,7 @@ void prof_clear(buzz_cache_t* c)
         v.clear();
     }
     c->prof_row_bytes = 0.0;
+    c->prof_evictions = 0;
 }
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? BUZZ_OK : BUZZ_EHIP; }
 
@@ -170,6 +185,23 @@ GatherArgs cache_gather_base(const buzz_cache_t* c)
     return g;
 }
 
+// Applies the score update the last decode step left pending, so that the scores are current.
+int flush_scores(buzz_cache_t* c, hipStream_t st)
+{
+    if (!c->pending || c->dry) { c->pending = false; return BUZZ_OK; }
+    const Layout& L = c->L;
+    AttnArgs a{};
+    a.score = c->at<float>(L.score);
+    a.logit_prev = c->at<float>(L.logit[c->last_buf]);
+    a.stat_prev = c->at<float>(L.stat[c->last_buf]);
+    a.map = c->map();
+    a.n = (int32_t)c->n();
+    a.cap = L.cap;
+    if (hipError_t e = launch_flush_scores(L.G, a, L.units, st, prof_pair(c, 1))) return hip_rc(e);
+    c->pending = false;
+    return BUZZ_OK;
+}
+
 // Alg. 1 lines 13-19 on the current state.
 int evict_impl(buzz_cache_t* c, hipStream_t st)
 {
@@ -183,21 +215,22 @@ int evict_impl(buzz_cache_t* c, hipStream_t st)
     const int64_t take_last = newc % s < keep ? newc % s : keep;
     const int64_t new2 = keep * (newc / s) + take_last;        // every segment yields min(keep, len)
     if (old2 + new2 > L.old_cap) return BUZZ_ECAPACITY;
+    if (int rc = flush_scores(c, st)) return rc;              // the selection reads the scores
     if (!c->dry) {
-        prof_mark(c, 2, st);
+        if (c->prof) c->prof_evictions += 1;
         if (old2 < c->n_old) {                                 // thin the old region through the staging rows
             GatherArgs g = cache_gather_base(c);
             g.src_start = (int32_t)k; g.src_step = (int32_t)sh;
             g.dstK = c->at<char>(L.stK); g.dstV = c->at<char>(L.stV);
             g.dstScore = c->at<float>(L.stScore); g.dstPos = c->at<int32_t>(L.stPos);
             g.dst_unit_rows = L.st_rows; g.dst_start = 0; g.n_rows = (int32_t)old2;
-            if (hipError_t e = launch_gather_rows(g, L.units, st)) return hip_rc(e);
+            if (hipError_t e = launch_gather_rows(g, L.units, st, prof_pair(c, 2))) return hip_rc(e);
             GatherArgs b = cache_gather_base(c);
             b.srcK = c->at<char>(L.stK); b.srcV = c->at<char>(L.stV);
             b.srcScore = c->at<float>(L.stScore); b.srcPos = c->at<int32_t>(L.stPos);
             b.src_unit_rows = L.st_rows; b.src_start = 0; b.src_step = 1;
             b.dst_start = (int32_t)k; b.n_rows = (int32_t)old2;
-            if (hipError_t e = launch_gather_rows(b, L.units, st)) return hip_rc(e);
+            if (hipError_t e = launch_gather_rows(b, L.units, st, prof_pair(c, 2))) return hip_rc(e);
         }
         if (new2 > 0) {
             SelectArgs sa{};
@@ -205,14 +238,13 @@ int evict_impl(buzz_cache_t* c, hipStream_t st)
             sa.map = c->map(); sa.lo = sa.map.front; sa.new_count = (int32_t)newc;
             sa.segment = cfg.segment; sa.keep = L.keep;
             sa.sel = c->at<int32_t>(L.sel); sa.sel_stride = L.sel_stride;
-            if (hipError_t e = launch_segment_topk(sa, L.units, st)) return hip_rc(e);
+            if (hipError_t e = launch_segment_topk(sa, L.units, st, prof_pair(c, 2))) return hip_rc(e);
             GatherArgs g = cache_gather_base(c);
             g.src_map = c->map();
             g.sel = c->at<int32_t>(L.sel); g.sel_stride = L.sel_stride; g.sel_start = 0; g.sel_step = 1;
             g.dst_start = (int32_t)(k + old2); g.n_rows = (int32_t)new2;
-            if (hipError_t e = launch_gather_rows(g, L.units, st)) return hip_rc(e);
+            if (hipError_t e = launch_gather_rows(g, L.units, st, prof_pair(c, 2))) return hip_rc(e);
         }
-        prof_mark(c, 2, st);
     }
     c->n_old = old2 + new2;
     c->head = (c->head + newc) % L.ring_cap;
@@ -254,8 +286,11 @@ int buzz_cache_create(const buzz_config_t* cfg, void* dev_workspace, size_t byte
     c->ready = false;
     c->sink_filled = c->n_old = c->tail = c->head = c->tokens_seen = 0;
     c->user_splits = 0;
+    c->pending = false;
+    c->last_buf = 0;
     c->prof = false;
     c->prof_row_bytes = 0.0;
+    c->prof_evictions = 0;
     *out = c;
     return BUZZ_OK;
 }
@@ -320,6 +355,7 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
 
     if (!c->dry) {
         float* ps = c->at<float>(L.pscore);
+        if (hipError_t e = launch_fill_f32(c->at<float>(L.ticket), nullptr, L.units, st)) return hip_rc(e);
         // starting scores, one row of N per unit
         if (hipError_t e = launch_fill_f32(ps, init_score, (int64_t)L.units * N, st)) return hip_rc(e);
         if (n_obs > 0) {
@@ -369,6 +405,7 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
             if (hipError_t e = launch_gather_rows(gt, L.units, st)) return hip_rc(e);
         }
     }
+    c->pending = false;
     c->sink_filled = sink_rows;
     c->n_old = survivors;
     c->tail = tail_rows;
@@ -402,7 +439,11 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         a.q = q; a.k_new = k_new; a.v_new = v_new;
         a.K = c->at<char>(L.K); a.V = c->at<char>(L.V);
         a.score = c->at<float>(L.score); a.pos = c->at<int32_t>(L.pos);
-        a.logit = c->at<float>(L.logit); a.part_ml = c->at<float>(L.part_ml); a.part_o = c->at<float>(L.part_o);
+        const int cur = c->last_buf ^ 1;
+        a.logit = c->at<float>(L.logit[cur]); a.logit_prev = c->at<float>(L.logit[c->last_buf]);
+        a.stat = c->at<float>(L.stat[cur]); a.stat_prev = c->at<float>(L.stat[c->last_buf]);
+        a.ticket = c->at<int32_t>(L.ticket); a.pending = c->pending ? 1 : 0;
+        a.part_ml = c->at<float>(L.part_ml); a.part_o = c->at<float>(L.part_o);
         a.out = out;
         a.map = c->map();
         a.map.front = (int32_t)(sink_filled + c->n_old);
@@ -413,6 +454,9 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         a.Hq = cfg.n_q_heads; a.Hkv = cfg.n_kv_heads;
         a.s_cap = L.s_cap;
         a.scale_log2 = c->scale * 1.4426950408889634f;
+        const double step_bytes = (double)L.units * (double)n * 2.0 * L.row_bytes;
+        a.streaming = (cfg.flags & BUZZ_FLAG_STREAMING) ? 1
+                      : (cfg.flags & BUZZ_FLAG_CACHED) ? 0 : (step_bytes > kLastLevelCacheBytes);
         const int tile = attn_tile_rows(cfg.kv_dtype, cfg.head_dim, L.G);
         int64_t S = c->user_splits > 0 ? c->user_splits : (kTargetBlocks + L.units / 2) / L.units;
         if (S < 1) S = 1;
@@ -420,14 +464,12 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
         a.rows_per_split = (int32_t)rps;
         a.n_splits = (int32_t)ceil_div(n, rps);
-        prof_mark(c, 0, st);
-        if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st)) return hip_rc(e);
-        prof_mark(c, 0, st);
+        if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st, prof_pair(c, 0)))
+            return hip_rc(e);
         if (c->prof) c->prof_row_bytes += (double)L.units * (double)n * 2.0 * L.row_bytes;
-        prof_mark(c, 1, st);
-        if (hipError_t e = launch_combine_score(cfg.head_dim, L.G, a, L.units, st)) return hip_rc(e);
-        prof_mark(c, 1, st);
+        c->last_buf = cur;
     }
+    c->pending = true;
     c->sink_filled = sink_filled;
     c->tail = tail;
     c->tokens_seen += 1;
@@ -447,6 +489,7 @@ int buzz_cache_export(buzz_cache_t* c, void* k, void* v, float* score, int32_t* 
     if (!alive(c)) return BUZZ_EINVAL;
     if (!c->ready) return BUZZ_ESTATE;
     if (c->dry) return BUZZ_OK;
+    if (int rc = flush_scores(c, (hipStream_t)hip_stream)) return rc;
     GatherArgs g = cache_gather_base(c);
     g.src_map = c->map();
     g.src_start = 0; g.src_step = 1;
@@ -478,7 +521,7 @@ int buzz_cache_profile_read(buzz_cache_t* c, buzz_profile_t* out)
             cnt[cls] += 1;
         }
     }
-    out->attn_launches = cnt[0]; out->epilogue_launches = cnt[1]; out->evictions = cnt[2];
+    out->attn_launches = cnt[0]; out->epilogue_launches = cnt[1]; out->evictions = c->prof_evictions;
     out->attn_ms = ms[0]; out->epilogue_ms = ms[1]; out->evict_ms = ms[2];
     out->attn_row_bytes = c->prof_row_bytes;
     return BUZZ_OK;

@@ -14,6 +14,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "buzz.h"
@@ -23,7 +24,8 @@ namespace buzz {
 constexpr int kMaxSplits = 128;        // upper bound on key-range splits per unit
 constexpr int kTargetBlocks = 1024;    // automatic split choice aims at this many blocks per launch
 constexpr int kMaxBlocks = 4096;       // partial buffers are sized for units * splits <= this (or 1 split per unit)
-constexpr int kMaxSegment = 4096;      // segment scores of one wave must fit its LDS slice
+constexpr int kMaxSegment = 4096;
+constexpr double kLastLevelCacheBytes = 256.0 * 1024 * 1024;   // Infinity Cache of one MI355X      // segment scores of one wave must fit its LDS slice
 
 struct RingMap {
     int32_t front;      // rows [0, front) are stored linearly
@@ -46,9 +48,13 @@ struct AttnArgs {
     void* V;
     float* score;        // [units][cap]
     int32_t* pos;        // [units][cap]
-    float* logit;        // [units][cap][G]  scaled logits in log2 units, written by the split kernel
+    float* logit;        // [units][G][cap]  scaled logits in log2 units, written by this step
+    const float* logit_prev;  // same layout: the previous step's logits (valid when pending)
     float* part_ml;      // [units][s_cap][G][2]  (running max, running sum) per split
     float* part_o;       // [units][s_cap][G][D]  unnormalised partial outputs per split
+    float* stat;         // [units][G][2]  this step's global (max, 1/sum), written by the merging block
+    const float* stat_prev;   // the previous step's
+    int32_t* ticket;     // [units] arrival counters, zero between launches
     float* out;          // [B][Hq][D]
     RingMap map;
     int32_t n;           // retained rows including the one being appended (logical index n-1)
@@ -59,6 +65,8 @@ struct AttnArgs {
     int32_t n_splits;
     int32_t s_cap;
     int32_t Hq, Hkv;
+    int32_t pending;     // 1: the previous step's score update has not been applied yet
+    int32_t streaming;   // 1: K/V are read with the non-temporal hint (working set exceeds the last-level cache)
     float scale_log2;    // softmax scale * log2(e)
 };
 
@@ -101,10 +109,20 @@ struct ObsArgs {               // prefill scoring: causal attention of observed 
 constexpr int kObsRows = 256;        // query rows (query x group member) per pass = threads per block
 constexpr int kObsKeyBlock = 1024;   // keys per block of the row-statistics kernel
 
-hipError_t launch_attn_split(int dtype, int D, int G, const AttnArgs& a, int units, hipStream_t st);
-hipError_t launch_combine_score(int D, int G, const AttnArgs& a, int units, hipStream_t st);
-hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st);
-hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st);
+// Optional event pair: when both are non-null the launch records the kernel's own begin / end
+// timestamps into them (used by the benchmark profiling pass).
+struct Timing { hipEvent_t begin = nullptr, end = nullptr; };
+
+#define BUZZ_LAUNCH(kernel, grid, block, lds, st, tm, ...)                                            \
+    do {                                                                                               \
+        if ((tm).begin) hipExtLaunchKernelGGL(kernel, grid, block, lds, st, (tm).begin, (tm).end, 0, __VA_ARGS__); \
+        else hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                            \
+    } while (0)
+
+hipError_t launch_attn_split(int dtype, int D, int G, const AttnArgs& a, int units, hipStream_t st, Timing tm = {});
+hipError_t launch_flush_scores(int G, const AttnArgs& a, int units, hipStream_t st, Timing tm = {});
+hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st, Timing tm = {});
+hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st, Timing tm = {});
 hipError_t launch_fill_f32(float* dst, const float* src, int64_t n, hipStream_t st);  // src NULL => zeros
 hipError_t launch_obs_scores(int dtype, int D, int G, const ObsArgs& a, int units, hipStream_t st);
 int attn_tile_rows(int dtype, int D, int G);   // rows one block consumes per loop trip (split sizes are multiples)

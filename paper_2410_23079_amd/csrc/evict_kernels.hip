@@ -88,21 +88,21 @@ __global__ __launch_bounds__(256) void fill_f32_kernel(float* dst, const float* 
 
 }  // namespace
 
-hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st)
+hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st, Timing tm)
 {
     const int n_seg = (a.new_count + a.segment - 1) / a.segment;
     if (n_seg <= 0) return hipSuccess;
     dim3 grid((n_seg + kSelWaves - 1) / kSelWaves, units), block(256);
     const size_t lds = (size_t)kSelWaves * a.segment * sizeof(float);
-    hipLaunchKernelGGL(segment_topk_kernel, grid, block, lds, st, a);
+    BUZZ_LAUNCH(segment_topk_kernel, grid, block, lds, st, tm, a);
     return hipGetLastError();
 }
 
-hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st)
+hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st, Timing tm)
 {
     if (a.n_rows <= 0) return hipSuccess;
     dim3 grid((a.n_rows + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock, units), block(256);
-    hipLaunchKernelGGL(gather_rows_kernel, grid, block, 0, st, a);
+    BUZZ_LAUNCH(gather_rows_kernel, grid, block, 0, st, tm, a);
     return hipGetLastError();
 }
 
