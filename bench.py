@@ -27,6 +27,8 @@ def parse():
     ap.add_argument("--workload", default="llama7b_layer")
     ap.add_argument("--layers", type=int, default=None, help="override the workload's layer count")
     ap.add_argument("--splits", type=int, default=0, help="key-range splits per unit (0 = automatic)")
+    ap.add_argument("--streaming", action="store_true",
+                    help="force streaming (non-temporal) K/V loads, as a cache that is one of many layers would use")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
@@ -105,7 +107,7 @@ def main():
               "batch and kv heads); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2410_23079_amd import FLAG_AUTO_EVICT
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_STREAMING
     from workloads import decode_inputs, get_workload
 
     wl = get_workload(args.workload)
@@ -119,7 +121,8 @@ def main():
     n_streams = min(layers, 4)                          # decode inputs: a few distinct seeded streams, reused over layers
     dec = [decode_inputs(wl, layer=i, device=device, steps=total) for i in range(n_streams)]
     out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device=device)
-    caches = make_caches(wl, layers, wl.prompt + total, args.splits, FLAG_AUTO_EVICT)
+    flags = FLAG_AUTO_EVICT | (FLAG_STREAMING if args.streaming else 0)
+    caches = make_caches(wl, layers, wl.prompt + total, args.splits, flags)
     prefill_all(wl, caches, device)
 
     run_steps(caches, dec, out, 0, warmup)
@@ -145,25 +148,28 @@ def main():
             c.profile(False)
         launches = sum(p["attn_launches"] for p in prof)
         attn_ms = sum(p["attn_ms"] for p in prof)
-        epi_ms = sum(p["epilogue_ms"] for p in prof)
+        flush_ms = sum(p["epilogue_ms"] for p in prof)
         ev_ms = sum(p["evict_ms"] for p in prof)
-        row_bytes = sum(p["attn_row_bytes"] for p in prof)
+        evictions = sum(p["evictions"] for p in prof)
+        kv_bytes = sum(p["attn_row_bytes"] for p in prof)            # sum over launches of units * n * 2 * D * e
         units = wl.batch * wl.n_kv_heads
-        rows = row_bytes / (units * 2 * wl.head_dim * (4 if wl.dtype == "fp32" else 2))   # sum of n over launches
-        achieved = row_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms else 0.0
+        elem = 4 if wl.dtype == "fp32" else 2
+        rows = kv_bytes / (units * 2 * wl.head_dim * elem)           # sum over launches of n
+        # algorithmic bytes of the attention + score pass: K and V rows plus the fp32 score read and write
+        algo_bytes = kv_bytes + units * rows * 8.0
+        achieved = algo_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms else 0.0
         traffic = None
         if args.traffic_kib:
             traffic = {"fetch_bytes": args.traffic_kib[0] * 1024, "write_bytes": args.traffic_kib[1] * 1024}
         roofline = {"bound": "hbm", "kernel": "attn_split_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "avg_launch_us": attn_ms * 1e3 / max(launches, 1),
-                    "bytes_per_launch": row_bytes / max(launches, 1), "traffic": traffic}
-        pass_bytes = row_bytes + units * rows * 8.0                       # + fp32 score read and write per row
-        extra = {"attn_plus_score_gbs": pass_bytes / ((attn_ms + epi_ms) * 1e-3) / 1e9 if attn_ms else 0.0,
-                 "epilogue_avg_us": epi_ms * 1e3 / max(launches, 1),
-                 "evict_avg_us": ev_ms * 1e3 / max(sum(p["evictions"] for p in prof), 1),
-                 "evict_time_over_attn_time": ev_ms / (attn_ms + epi_ms) if attn_ms else 0.0}
-        extra["attn_plus_score_frac"] = extra["attn_plus_score_gbs"] / HBM_PEAK_GBS
+                    "avg_launch_us": attn_ms * 1e3 / max(launches, 1), "launches": launches,
+                    "bytes_per_launch": algo_bytes / max(launches, 1), "traffic": traffic}
+        extra = {"evictions": evictions,
+                 "evict_avg_us": (ev_ms + flush_ms) * 1e3 / max(evictions, 1),
+                 "evict_time_over_attn_time": (ev_ms + flush_ms) / attn_ms if attn_ms else 0.0,
+                 "step_bytes_over_peak_over_step_time": (algo_bytes / max(launches, 1) * layers / HBM_PEAK_GBS / 1e9)
+                                                        / (elapsed / steps)}
 
     base = None if args.no_cpu_baseline else cpu_baseline(wl)
     line = {
@@ -174,7 +180,8 @@ def main():
         "config": {"workload": wl.name, "layers": layers, "batch": wl.batch, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "prompt": wl.prompt, "sink": wl.sink,
                    "window": wl.window, "segment": wl.segment, "keep": wl.keep, "evict_every": wl.evict_every,
-                   "old_stride": wl.old_stride, "retained_rows_end": n_end, "splits": args.splits or "auto"},
+                   "old_stride": wl.old_stride, "retained_rows_end": n_end, "splits": args.splits or "auto",
+                   "kv_loads": "streaming" if args.streaming else "auto"},
         "roofline": roofline, "cpu_baseline": base,
     }
     line.update(extra)

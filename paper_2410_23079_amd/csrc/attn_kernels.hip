@@ -38,9 +38,6 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 #ifndef BUZZ_U_G8
 #define BUZZ_U_G8 2
 #endif
-#ifndef BUZZ_PREFETCH
-#define BUZZ_PREFETCH 0  // 1: issue the next trip's loads before computing the current one
-#endif
 #ifndef BUZZ_MIN_BLOCKS
 #define BUZZ_MIN_BLOCKS 1  // second argument of __launch_bounds__
 #endif
@@ -122,6 +119,12 @@ template <int LPR> __device__ inline float row_sum(float v) {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Split partials travel between blocks (possibly on different XCDs, each with its own L2) inside one
+// launch.  They are written and read with device-scope atomic accesses, which go through to the
+// memory side instead of staying in an XCD's L2, so no cache write-back or invalidate is needed.
+__device__ inline void publish(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ inline float acquire(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
 // A split's logical row range is cut into at most four physically contiguous runs (linear region,
 // ring before the wrap, ring after the wrap, the row being appended), so the streaming loop only
 // advances pointers.  Within a run the block's four waves take tiles of WROWS rows round-robin.
@@ -137,9 +140,9 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
     constexpr int WROWS = RPW * U;        // rows one wave consumes per trip
     constexpr int TILE = NW * WROWS;
     static_assert(LPR >= 8 && LPR <= 64, "row must span 8..64 lanes");
-    static_assert(WROWS <= 64, "one lane per row when the logits are written out");
+    static_assert((WROWS & (WROWS - 1)) == 0, "tiles anchor at multiples of WROWS");
 
-    __shared__ float sm_logit[NW][G][WROWS];
+    extern __shared__ float stage[];                      // [G][rows_per_split] logits of this split's rows
     __shared__ float sm_m[NW][G], sm_l[NW][G];
     __shared__ float sm_acc[NW][G][D];
     __shared__ float sm_w[kMaxSplits][G], sm_pl[kMaxSplits][G];
@@ -180,45 +183,36 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
         for (int v = 0; v < VEC; ++v) acc[g][v] = 0.f;
     }
 
-    // rows of the run that this lane loads in the trip starting at `base`; masked lanes re-read the run's last row
-    auto load_tile = [&](u32x4 (&kr)[U], u32x4 (&vr)[U], const char* kp, const char* vp, int base, int cnt) {
+    // Work split inside a block.  A split's logical row range is cut into at most four physically
+    // contiguous runs; inside a run every wave owns one contiguous sub-range and walks it in tiles of
+    // WROWS rows on a grid anchored at a physical multiple of WROWS (`lead` rows before the run's first
+    // row are masked).  The streaming phase only reads: logits are staged in LDS, and all per-row side
+    // traffic (this step's logits out, the previous step's logits and the old score in, the new score out)
+    // happens in one dense phase at the end of the block.  Writes that trickle into a saturated read
+    // stream were measured to cost ~5% of the kernel per 1% of extra bytes.
+    auto load_tile = [&](u32x4 (&kr)[U], u32x4 (&vr)[U], const char* kp, const char* vp, int base, int lead, int cnt) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const unsigned off = (unsigned)min(base + u * RPW + rs, cnt - 1) * ROWB + lane_off;
+        for (int u = 0; u < U; ++u) {      // masked lanes re-read a valid row of the run
+            const unsigned off = (unsigned)(min(max(base + u * RPW + rs, lead), cnt - 1) - lead) * ROWB + lane_off;
             kr[u] = load16<NT>(kp + off);
             vr[u] = load16<NT>(vp + off);
         }
     };
 
-    auto compute_tile = [&](const u32x4 (&kr)[U], const u32x4 (&vr)[U], int base, int cnt, int phys0, bool fresh) {
+    // `stg` = staging index (row relative to the split's first row) of the tile's first row
+    auto compute_tile = [&](const u32x4 (&kr)[U], const u32x4 (&vr)[U], int base, int lead, int cnt, int stg) {
         float s[G][U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool ok = base + u * RPW + rs < cnt;
+            const int r = base + u * RPW + rs;
+            const bool ok = r >= lead && r < cnt;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const float d = row_sum<LPR>(E::dot(qr[g], kr[u])) * a.scale_log2;
                 s[g][u] = ok ? d : -INFINITY;
-                if (c == 0) sm_logit[wave][g][u * RPW + rs] = d;
+                if (c == 0 && ok) stage[g * a.rows_per_split + stg + u * RPW + rs] = d;
             }
         }
-        // one lane per row (LDS ops of a wave complete in order): coalesced store of the trip's logits and
-        // the previous step's pending score update; a freshly appended row starts from score 0
-        __builtin_amdgcn_wave_barrier();
-        if (lane < WROWS && base + lane < cnt) {
-            const int ph = phys0 + base + lane;
-#pragma unroll
-            for (int g = 0; g < G; ++g) logit_u[(size_t)g * a.cap + ph] = sm_logit[wave][g][lane];
-            if (fresh) {
-                score_u[ph] = 0.f;
-            } else if (a.pending) {
-                float sc = score_u[ph];
-#pragma unroll
-                for (int g = 0; g < G; ++g) sc += fast_exp2(logit_prev_u[(size_t)g * a.cap + ph] - Mp[g]) * iLp[g];
-                score_u[ph] = sc;
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
         // online softmax: s becomes the unnormalised probability relative to the running maximum
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -256,15 +250,21 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
     const int jl1 = min(j1, a.n - 1);                     // rows already stored in the arena end here
     const int wrap = a.map.front + a.map.ring_cap - a.map.ring_head;   // first logical row after the ring wraps
 
-    for (int run = 0; run < 4; ++run) {
-        int lo, hi, phys0;
-        const char *kp, *vp;
+    // run r covers logical rows [lo, hi) stored at physical rows phys0 ...; run 3 is the row being appended
+    auto run_bounds = [&](int run, int& lo, int& hi, int& phys0) {
         if (run == 0) { lo = j0; hi = min(jl1, a.map.front); phys0 = lo; }
         else if (run == 1) { lo = max(j0, a.map.front); hi = min(jl1, wrap); phys0 = a.map.ring_base + a.map.ring_head + (lo - a.map.front); }
         else if (run == 2) { lo = max(j0, wrap); hi = jl1; phys0 = a.map.ring_base + (lo - wrap); }
         else { lo = a.n - 1; hi = j1 == a.n ? a.n : lo; phys0 = a.new_phys; }
-        const int cnt = hi - lo;
-        if (cnt <= 0) continue;
+    };
+
+    for (int run = 0; run < 4; ++run) {
+        int lo, hi, phys0;
+        run_bounds(run, lo, hi, phys0);
+        if (hi - lo <= 0) continue;
+        const char *kp, *vp;
+        const int lead = phys0 & (WROWS - 1);             // rows between the aligned anchor and the run's first row
+        const int cnt = hi - lo + lead;                   // run length measured from the anchor
         if (run < 3) {
             kp = Kb + (size_t)phys0 * ROWB;
             vp = Vb + (size_t)phys0 * ROWB;
@@ -277,28 +277,13 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
                 if (c == 0) a.pos[ubase + a.new_phys] = a.new_pos;
             }
         }
-#if BUZZ_PREFETCH
-        u32x4 ka[U], va[U], kb[U], vb[U];
-        int base = wave * WROWS;
-        if (base < cnt) load_tile(ka, va, kp, vp, base, cnt);
-        while (base < cnt) {
-            int nb = base + TILE;
-            if (nb < cnt) load_tile(kb, vb, kp, vp, nb, cnt);
-            compute_tile(ka, va, base, cnt, phys0, run == 3);
-            base = nb;
-            if (base >= cnt) break;
-            nb = base + TILE;
-            if (nb < cnt) load_tile(ka, va, kp, vp, nb, cnt);
-            compute_tile(kb, vb, base, cnt, phys0, run == 3);
-            base = nb;
-        }
-#else
-        for (int base = wave * WROWS; base < cnt; base += TILE) {
+        const int per = ((cnt + NW - 1) / NW + WROWS - 1) / WROWS * WROWS;   // rows per wave, whole tiles
+        const int w1 = min(cnt, (wave + 1) * per);
+        for (int base = wave * per; base < w1; base += WROWS) {
             u32x4 kr[U], vr[U];
-            load_tile(kr, vr, kp, vp, base, cnt);
-            compute_tile(kr, vr, base, cnt, phys0, run == 3);
+            load_tile(kr, vr, kp, vp, base, lead, cnt);
+            compute_tile(kr, vr, base, lead, cnt, lo - j0 + base - lead);
         }
-#endif
     }
 
     // merge the RPW lane groups of this wave (same columns, different rows)
@@ -348,26 +333,75 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
             o = fmaf(wgt, sm_acc[w][g][d], o);
             L = fmaf(wgt, sm_l[w][g], L);
         }
-        a.part_o[(pbase + g) * D + d] = o;
+        publish(a.part_o + (pbase + g) * D + d, o);
         if (d == 0) {
-            a.part_ml[(pbase + g) * 2] = M;
-            a.part_ml[(pbase + g) * 2 + 1] = L;
+            publish(a.part_ml + (pbase + g) * 2, M);
+            publish(a.part_ml + (pbase + g) * 2 + 1, L);
         }
     }
 
-    // ticket: the block that arrives last for this unit sees every split's partial and merges them
+    // Dense side phase (the logits staged by all waves are visible after the barrier above).  Four
+    // consecutive physical rows per thread, 16-byte accesses where a whole group belongs to this split.
+    for (int run = 0; run < 4; ++run) {
+        int lo, hi, phys0;
+        run_bounds(run, lo, hi, phys0);
+        if (hi - lo <= 0) continue;
+        const bool fresh = run == 3;                      // the appended row starts from score 0
+        const bool upd = a.pending && !fresh;
+        const int lead = phys0 & 3, pa = phys0 - lead, cnt = hi - lo + lead;
+        for (int r0 = 4 * tid; r0 < cnt; r0 += 4 * 256) {
+            const int ph = pa + r0;
+            float4 sc = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (upd) {
+                sc = *(const float4*)(score_u + ph);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const float4 lp = *(const float4*)(logit_prev_u + (size_t)g * a.cap + ph);
+                    sc.x += fast_exp2(lp.x - Mp[g]) * iLp[g];
+                    sc.y += fast_exp2(lp.y - Mp[g]) * iLp[g];
+                    sc.z += fast_exp2(lp.z - Mp[g]) * iLp[g];
+                    sc.w += fast_exp2(lp.w - Mp[g]) * iLp[g];
+                }
+            }
+            const int sj = lo - j0 + r0 - lead;           // staging index of the group's first row
+            if (r0 >= lead && r0 + 3 < cnt) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const float* sg = stage + g * a.rows_per_split + sj;
+                    *(float4*)(logit_u + (size_t)g * a.cap + ph) = make_float4(sg[0], sg[1], sg[2], sg[3]);
+                }
+                if (upd || fresh) *(float4*)(score_u + ph) = sc;
+            } else {                                      // ragged edge of the run: row by row
+                const float scv[4] = {sc.x, sc.y, sc.z, sc.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (r0 + e >= lead && r0 + e < cnt) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) logit_u[(size_t)g * a.cap + ph + e] = stage[g * a.rows_per_split + sj + e];
+                        if (upd || fresh) score_u[ph + e] = scv[e];
+                    }
+                }
+            }
+        }
+    }
+
+    // ticket: the block that arrives last for this unit sees every split's partial and merges them.
+    // Every wave first waits until its own published (write-through) stores have been acknowledged
+    // (vmcnt(0)), then the block synchronises, then one thread takes the ticket: the ticket can never
+    // overtake a partial.  No cache maintenance is involved.
     const int S = a.n_splits;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0), expcnt / lgkmcnt untouched
     __syncthreads();
-    if (tid == 0) sm_ticket = atomicAdd(a.ticket + unit, 1);
+    if (tid == 0) sm_ticket = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (sm_ticket != S - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    if (tid == 0) a.ticket[unit] = 0;                     // ready for the next step
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (tid == 0) __hip_atomic_store(a.ticket + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next step
     const float* ml = a.part_ml + (size_t)unit * a.s_cap * G * 2;
     for (int i = tid; i < S * G; i += 256) {
-        sm_w[i / G][i % G] = ml[i * 2];
-        sm_pl[i / G][i % G] = ml[i * 2 + 1];
+        sm_w[i / G][i % G] = acquire(ml + i * 2);
+        sm_pl[i / G][i % G] = acquire(ml + i * 2 + 1);
     }
     __syncthreads();
     if (tid < G) {
@@ -394,11 +428,11 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
         for (; sp + 8 <= S; sp += 8) {                    // eight independent loads in flight
             float x[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = po[((size_t)(sp + e) * G + g) * D + d];
+            for (int e = 0; e < 8; ++e) x[e] = acquire(po + ((size_t)(sp + e) * G + g) * D + d);
 #pragma unroll
             for (int e = 0; e < 8; ++e) o = fmaf(sm_w[sp + e][g], x[e], o);
         }
-        for (; sp < S; ++sp) o = fmaf(sm_w[sp][g], po[((size_t)sp * G + g) * D + d], o);
+        for (; sp < S; ++sp) o = fmaf(sm_w[sp][g], acquire(po + ((size_t)sp * G + g) * D + d), o);
         outp[(size_t)g * D + d] = o * sm_invL[g];
     }
 }
@@ -435,8 +469,11 @@ template <typename T, int D, int G>
 hipError_t launch_split_t(const AttnArgs& a, int units, hipStream_t st, Timing tm)
 {
     dim3 grid(a.n_splits, units), block(256);
-    if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, unroll_for<G>(), true>), grid, block, 0, st, tm, a);
-    else BUZZ_LAUNCH((attn_split_kernel<T, D, G, unroll_for<G>(), false>), grid, block, 0, st, tm, a);
+    constexpr int RPW = 64 / (D / Elem<T>::VEC);
+    constexpr int U = unroll_for<G>() * RPW >= 4 ? unroll_for<G>() : 4 / RPW;   // a trip covers at least 4 rows
+    const size_t lds = (size_t)G * a.rows_per_split * sizeof(float);   // logit staging
+    if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, true>), grid, block, lds, st, tm, a);
+    else BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, false>), grid, block, lds, st, tm, a);
     return hipGetLastError();
 }
 
@@ -476,7 +513,8 @@ int attn_tile_rows(int dtype, int D, int G)
 {
     const int vec = dtype == BUZZ_FP32 ? 4 : 8;
     const int rpw = 64 / (D / vec);
-    const int u = G == 1 ? BUZZ_U_G1 : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
+    int u = G == 1 ? BUZZ_U_G1 : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
+    if (u * rpw < 4) u = 4 / rpw;
     return 4 * rpw * u;
 }
 

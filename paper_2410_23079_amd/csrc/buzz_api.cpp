@@ -69,6 +69,9 @@ int make_layout(const buzz_config_t* c, Layout* L)
     int64_t s_cap = kMaxBlocks / units;
     if (s_cap < 1) s_cap = 1;
     if (s_cap > kMaxSplits) s_cap = kMaxSplits;
+    const int64_t s_need = ceil_div(cap * G, kStageFloats) + 1;   // a split's logits must fit the LDS staging
+    if (s_need > kMaxSplits) return BUZZ_EUNSUPPORTED;
+    if (s_cap < s_need) s_cap = s_need;
     L->s_cap = (int32_t)s_cap;
     const int64_t sel_bound = keep * (ceil_div(M, s) + 1);
     L->sel_stride = (int32_t)(keep == 0 ? 1 : (sel_bound < M ? sel_bound : (M > 0 ? M : 1)));
@@ -143,6 +146,21 @@ struct buzz_cache {
 namespace {
 
 inline bool alive(const buzz_cache_t* c) { return c && c->magic == kMagic; }
+
+// compute units of the current device (queried once, at the first launch)
+int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+        else
+            cus = kDefaultCUs;
+    }
+    return cus;
+}
 
 constexpr size_t kMaxProfEvents = 1 << 15;
 
@@ -458,10 +476,16 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         a.streaming = (cfg.flags & BUZZ_FLAG_STREAMING) ? 1
                       : (cfg.flags & BUZZ_FLAG_CACHED) ? 0 : (step_bytes > kLastLevelCacheBytes);
         const int tile = attn_tile_rows(cfg.kv_dtype, cfg.head_dim, L.G);
-        int64_t S = c->user_splits > 0 ? c->user_splits : (kTargetBlocks + L.units / 2) / L.units;
+        // few, long blocks amortise the per-block merge; a block count that fills every compute unit the same
+        // number of times avoids a tail: floor(2 * CUs / units) splits
+        int64_t S = c->user_splits > 0 ? c->user_splits : (int64_t)kBlocksPerCU * compute_units() / L.units;
         if (S < 1) S = 1;
         if (S > L.s_cap) S = L.s_cap;
         int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
+        while (rps * L.G > kStageFloats) {                     // LDS staging bound; s_cap was sized for this
+            S += 1;
+            rps = ceil_div(ceil_div(n, S), tile) * tile;
+        }
         a.rows_per_split = (int32_t)rps;
         a.n_splits = (int32_t)ceil_div(n, rps);
         if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st, prof_pair(c, 0)))

@@ -22,9 +22,11 @@
 namespace buzz {
 
 constexpr int kMaxSplits = 128;        // upper bound on key-range splits per unit
-constexpr int kTargetBlocks = 1024;    // automatic split choice aims at this many blocks per launch
+constexpr int kBlocksPerCU = 2;        // automatic split choice: units * splits <= this many blocks per compute unit
+constexpr int kDefaultCUs = 256;       // MI355X; replaced by the device's own count at the first launch
 constexpr int kMaxBlocks = 4096;       // partial buffers are sized for units * splits <= this (or 1 split per unit)
 constexpr int kMaxSegment = 4096;
+constexpr int kStageFloats = 4096;     // LDS logit staging of one split: rows_per_split * group size <= this
 constexpr double kLastLevelCacheBytes = 256.0 * 1024 * 1024;   // Infinity Cache of one MI355X      // segment scores of one wave must fit its LDS slice
 
 struct RingMap {
