@@ -31,8 +31,9 @@ def parse():
                     help="force streaming (non-temporal) K/V loads, as a cache that is one of many layers would use")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
-    ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
-                    help="rocprofv3 FETCH_SIZE / WRITE_SIZE per attention launch (scaled KiB) to report as traffic")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run the library's plain copy kernel once on this many MiB (for rocprofv3 --pmc runs: "
+                         "its known size gives the scale of the byte counters)")
     return ap.parse_args()
 
 
@@ -125,6 +126,13 @@ def main():
     caches = make_caches(wl, layers, wl.prompt + total, args.splits, flags)
     prefill_all(wl, caches, device)
 
+    if args.copy_calibration_mib:
+        from paper_2410_23079_amd import bench_copy
+        src = torch.full((args.copy_calibration_mib << 20,), 7, dtype=torch.uint8, device=device)
+        dst = torch.empty_like(src)
+        bench_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     run_steps(caches, dec, out, 0, warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -158,9 +166,13 @@ def main():
         # algorithmic bytes of the attention + score pass: K and V rows plus the fp32 score read and write
         algo_bytes = kv_bytes + units * rows * 8.0
         achieved = algo_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms else 0.0
-        traffic = None
-        if args.traffic_kib:
-            traffic = {"fetch_bytes": args.traffic_kib[0] * 1024, "write_bytes": args.traffic_kib[1] * 1024}
+        traffic = None                                             # HBM bytes per launch from rocprofv3 --pmc runs
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath):
+            t = json.load(open(tpath)).get(wl.name)
+            if t and layers == wl.layers and not args.splits:
+                traffic = {"fetch_bytes": t["fetch_bytes_per_launch"], "write_bytes": t["write_bytes_per_launch"],
+                           "source": t["source"]}
         roofline = {"bound": "hbm", "kernel": "attn_split_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "avg_launch_us": attn_ms * 1e3 / max(launches, 1), "launches": launches,

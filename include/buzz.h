@@ -190,6 +190,14 @@ typedef struct buzz_profile {
 int buzz_cache_profile(buzz_cache_t* cache, int enable);
 int buzz_cache_profile_read(buzz_cache_t* cache, buzz_profile_t* out);
 
+/*
+ * Benchmark aid: a plain 16-byte-per-thread device-to-device copy of `bytes` bytes (multiple of 16,
+ * both pointers 16-byte aligned, ranges must not overlap).  A copy of known size gives the factor by
+ * which a hardware byte counter (FETCH_SIZE, WRITE_SIZE) has to be scaled on this machine.
+ * Errors: BUZZ_EINVAL, BUZZ_EHIP.
+ */
+int buzz_bench_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
 /* Static description of a status code (host string, never NULL). */
 const char* buzz_strerror(int status);
 

@@ -1,6 +1,6 @@
 """MI355X-native BUZZ sparse-KV-cache decode path (arxiv 2410.23079): thin Python binding over ``libbuzz.so``."""
-from .binding import (BuzzCache, BuzzConfig, BuzzError, FLAG_AUTO_EVICT, FLAG_CACHED, FLAG_DRY_RUN, FLAG_STREAMING, library_path, load_library,
+from .binding import (bench_copy, BuzzCache, BuzzConfig, BuzzError, FLAG_AUTO_EVICT, FLAG_CACHED, FLAG_DRY_RUN, FLAG_STREAMING, library_path, load_library,
                       workspace_bytes)
 
-__all__ = ["BuzzCache", "BuzzConfig", "BuzzError", "FLAG_AUTO_EVICT", "FLAG_CACHED", "FLAG_DRY_RUN", "FLAG_STREAMING", "library_path",
+__all__ = ["bench_copy", "BuzzCache", "BuzzConfig", "BuzzError", "FLAG_AUTO_EVICT", "FLAG_CACHED", "FLAG_DRY_RUN", "FLAG_STREAMING", "library_path",
            "load_library", "workspace_bytes"]

@@ -22,7 +22,7 @@ DTYPE_CODES = {"fp32": 0, "fp16": 1, "bf16": 2}
 
 EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step", "buzz_evict",
            "buzz_cache_destroy", "buzz_cache_len", "buzz_cache_export", "buzz_cache_set_splits", "buzz_cache_profile",
-           "buzz_cache_profile_read", "buzz_strerror"]
+           "buzz_cache_profile_read", "buzz_bench_copy", "buzz_strerror"]
 
 
 class BuzzError(RuntimeError):
@@ -100,6 +100,7 @@ def load_library():
     lib.buzz_cache_set_splits.argtypes = [P, ctypes.c_int32]
     lib.buzz_cache_profile.argtypes = [P, ctypes.c_int]
     lib.buzz_cache_profile_read.argtypes = [P, ctypes.POINTER(_Profile)]
+    lib.buzz_bench_copy.argtypes = [P, P, ctypes.c_size_t, P]
     lib.buzz_strerror.argtypes = [ctypes.c_int]
     lib.buzz_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -116,6 +117,12 @@ def workspace_bytes(cfg: BuzzConfig) -> int:
     c = cfg.to_c()
     _check(load_library().buzz_workspace_bytes(ctypes.byref(c), ctypes.byref(out)), "buzz_workspace_bytes")
     return out.value
+
+
+def bench_copy(dst, src, stream=None):
+    """Plain device copy of ``src`` into ``dst`` (same byte size) with the library's own copy kernel."""
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().buzz_bench_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)), "buzz_bench_copy")
 
 
 def _ptr(t):

@@ -551,6 +551,12 @@ int buzz_cache_profile_read(buzz_cache_t* c, buzz_profile_t* out)
     return BUZZ_OK;
 }
 
+int buzz_bench_copy(void* dst, const void* src, size_t bytes, void* hip_stream)
+{
+    if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return BUZZ_EINVAL;
+    return hip_rc(launch_plain_copy(dst, src, bytes, (hipStream_t)hip_stream));
+}
+
 const char* buzz_strerror(int status)
 {
     switch (status) {

@@ -126,6 +126,7 @@ hipError_t launch_flush_scores(int G, const AttnArgs& a, int units, hipStream_t 
 hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st, Timing tm = {});
 hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st, Timing tm = {});
 hipError_t launch_fill_f32(float* dst, const float* src, int64_t n, hipStream_t st);  // src NULL => zeros
+hipError_t launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_obs_scores(int dtype, int D, int G, const ObsArgs& a, int units, hipStream_t st);
 int attn_tile_rows(int dtype, int D, int G);   // rows one block consumes per loop trip (split sizes are multiples)
 bool attn_supported(int dtype, int D, int G);

@@ -86,7 +86,23 @@ __global__ __launch_bounds__(256) void fill_f32_kernel(float* dst, const float* 
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src ? src[i] : 0.f;
 }
 
+__global__ __launch_bounds__(256) void plain_copy_kernel(uint4* dst, const uint4* src, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
+
+hipError_t launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(plain_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint4*)dst, (const uint4*)src, n16);
+    return hipGetLastError();
+}
 
 hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st, Timing tm)
 {
