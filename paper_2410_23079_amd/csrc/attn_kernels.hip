@@ -145,8 +145,6 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
     extern __shared__ float stage[];                      // [G][rows_per_split] logits of this split's rows
     __shared__ float sm_m[NW][G], sm_l[NW][G];
     __shared__ float sm_acc[NW][G][D];
-    __shared__ float sm_w[kMaxSplits][G], sm_pl[kMaxSplits][G];
-    __shared__ float sm_M[G], sm_invL[G];
     __shared__ int sm_ticket;
 
     const int split = blockIdx.x, unit = blockIdx.y;
@@ -319,6 +317,8 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
         }
     }
     __syncthreads();
+    const int S = a.n_splits;
+    float* outp = a.out + (size_t)(b * a.Hq + kvh * G) * D;
     const size_t pbase = ((size_t)unit * a.s_cap + split) * G;
     for (int i = tid; i < G * D; i += 256) {
         const int g = i / D, d = i - g * D;
@@ -333,20 +333,45 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
             o = fmaf(wgt, sm_acc[w][g][d], o);
             L = fmaf(wgt, sm_l[w][g], L);
         }
-        publish(a.part_o + (pbase + g) * D + d, o);
-        if (d == 0) {
-            publish(a.part_ml + (pbase + g) * 2, M);
-            publish(a.part_ml + (pbase + g) * 2 + 1, L);
+        if (S == 1) {                                     // the only split: this is the result
+            outp[(size_t)g * D + d] = o / L;
+            if (d == 0) {
+                a.stat[((size_t)unit * G + g) * 2] = M;
+                a.stat[((size_t)unit * G + g) * 2 + 1] = 1.0f / L;
+            }
+        } else {
+            publish(a.part_o + (pbase + g) * D + d, o);
+            if (d == 0) {
+                publish(a.part_ml + (pbase + g) * 2, M);
+                publish(a.part_ml + (pbase + g) * 2 + 1, L);
+            }
         }
     }
 
-    // Dense side phase (the logits staged by all waves are visible after the barrier above).  Four
-    // consecutive physical rows per thread, 16-byte accesses where a whole group belongs to this split.
+    // Ticket: the block that arrives last for this unit sees every split's partial and merges them.
+    // Every wave first waits until its own published (write-through) stores have been acknowledged
+    // (vmcnt(0)), then the block synchronises, then one thread takes the ticket: the ticket can never
+    // overtake a partial.  No cache maintenance is involved.  The ticket's round trip overlaps with the
+    // side phase below; its value is only looked at afterwards.
+    int my_ticket = 0;
+    if (S > 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0), expcnt / lgkmcnt untouched
+        __syncthreads();
+        if (tid == 0) my_ticket = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // Dense side phase, after the read stream of this block is over (the logits staged by all waves are
+    // visible after the barrier that followed the wave merge).  Four consecutive physical rows per thread,
+    // 16-byte accesses where the whole group belongs to this split: this step's logits go out, and the
+    // previous step's pending score update is applied; the appended row starts from score 0.
+    // (Doing the score update at the start of the block instead, under the latency of the first K/V
+    // loads, was measured 8% slower: its writes then compete with the ramping read stream.)
     for (int run = 0; run < 4; ++run) {
         int lo, hi, phys0;
         run_bounds(run, lo, hi, phys0);
         if (hi - lo <= 0) continue;
-        const bool fresh = run == 3;                      // the appended row starts from score 0
+        const bool fresh = run == 3;
         const bool upd = a.pending && !fresh;
         const int lead = phys0 & 3, pa = phys0 - lead, cnt = hi - lo + lead;
         for (int r0 = 4 * tid; r0 < cnt; r0 += 4 * 256) {
@@ -354,13 +379,15 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
             float4 sc = make_float4(0.f, 0.f, 0.f, 0.f);
             if (upd) {
                 sc = *(const float4*)(score_u + ph);
+                float4 lp[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) lp[g] = *(const float4*)(logit_prev_u + (size_t)g * a.cap + ph);
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    const float4 lp = *(const float4*)(logit_prev_u + (size_t)g * a.cap + ph);
-                    sc.x += fast_exp2(lp.x - Mp[g]) * iLp[g];
-                    sc.y += fast_exp2(lp.y - Mp[g]) * iLp[g];
-                    sc.z += fast_exp2(lp.z - Mp[g]) * iLp[g];
-                    sc.w += fast_exp2(lp.w - Mp[g]) * iLp[g];
+                    sc.x += fast_exp2(lp[g].x - Mp[g]) * iLp[g];
+                    sc.y += fast_exp2(lp[g].y - Mp[g]) * iLp[g];
+                    sc.z += fast_exp2(lp[g].z - Mp[g]) * iLp[g];
+                    sc.w += fast_exp2(lp[g].w - Mp[g]) * iLp[g];
                 }
             }
             const int sj = lo - j0 + r0 - lead;           // staging index of the group's first row
@@ -385,55 +412,45 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
         }
     }
 
-    // ticket: the block that arrives last for this unit sees every split's partial and merges them.
-    // Every wave first waits until its own published (write-through) stores have been acknowledged
-    // (vmcnt(0)), then the block synchronises, then one thread takes the ticket: the ticket can never
-    // overtake a partial.  No cache maintenance is involved.
-    const int S = a.n_splits;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0), expcnt / lgkmcnt untouched
-    __syncthreads();
-    if (tid == 0) sm_ticket = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (S == 1) return;
+    if (tid == 0) sm_ticket = my_ticket;
     __syncthreads();
     if (sm_ticket != S - 1) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     if (tid == 0) __hip_atomic_store(a.ticket + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next step
+    // one round of loads: every thread fetches the (max, sum) of all splits for its head together with
+    // its column of the partial outputs, and derives the merge weights itself
     const float* ml = a.part_ml + (size_t)unit * a.s_cap * G * 2;
-    for (int i = tid; i < S * G; i += 256) {
-        sm_w[i / G][i % G] = acquire(ml + i * 2);
-        sm_pl[i / G][i % G] = acquire(ml + i * 2 + 1);
-    }
-    __syncthreads();
-    if (tid < G) {
-        float M = -INFINITY;
-        for (int sp = 0; sp < S; ++sp) M = fmaxf(M, sm_w[sp][tid]);
-        float L = 0.f;
-        for (int sp = 0; sp < S; ++sp) {
-            const float w = fast_exp2(sm_w[sp][tid] - M);  // M is finite: the appended row is always present
-            sm_w[sp][tid] = w;
-            L = fmaf(sm_pl[sp][tid], w, L);
-        }
-        sm_M[tid] = M;
-        sm_invL[tid] = 1.0f / L;
-        a.stat[((size_t)unit * G + tid) * 2] = M;
-        a.stat[((size_t)unit * G + tid) * 2 + 1] = 1.0f / L;
-    }
-    __syncthreads();
     const float* po = a.part_o + (size_t)unit * a.s_cap * G * D;
-    float* outp = a.out + (size_t)(b * a.Hq + kvh * G) * D;
     for (int i = tid; i < G * D; i += 256) {
         const int g = i / D, d = i - g * D;
-        float o = 0.f;
-        int sp = 0;
-        for (; sp + 8 <= S; sp += 8) {                    // eight independent loads in flight
-            float x[8];
+        float M = -INFINITY, L = 0.f, o = 0.f;
+        for (int sp0 = 0; sp0 < S; sp0 += 8) {
+            float ms[8], ls[8], xs[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = acquire(po + ((size_t)(sp + e) * G + g) * D + d);
+            for (int e = 0; e < 8; ++e) {
+                const int sp = min(sp0 + e, S - 1);
+                ms[e] = acquire(ml + ((size_t)sp * G + g) * 2);
+                ls[e] = acquire(ml + ((size_t)sp * G + g) * 2 + 1);
+                xs[e] = acquire(po + ((size_t)sp * G + g) * D + d);
+            }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o = fmaf(sm_w[sp + e][g], x[e], o);
+            for (int e = 0; e < 8; ++e) {
+                if (sp0 + e < S) {                        // online merge: M is finite after the first split with rows
+                    const float mn = fmaxf(M, ms[e]);
+                    const float mref = (mn == -INFINITY) ? 0.f : mn;
+                    const float wo = fast_exp2(M - mref), wn = fast_exp2(ms[e] - mref);
+                    o = o * wo + xs[e] * wn;
+                    L = L * wo + ls[e] * wn;
+                    M = mn;
+                }
+            }
         }
-        for (; sp < S; ++sp) o = fmaf(sm_w[sp][g], acquire(po + ((size_t)sp * G + g) * D + d), o);
-        outp[(size_t)g * D + d] = o * sm_invL[g];
+        outp[(size_t)g * D + d] = o / L;
+        if (d == 0) {
+            a.stat[((size_t)unit * G + g) * 2] = M;
+            a.stat[((size_t)unit * G + g) * 2 + 1] = 1.0f / L;
+        }
     }
 }
 

@@ -69,7 +69,7 @@ int make_layout(const buzz_config_t* c, Layout* L)
     int64_t s_cap = kMaxBlocks / units;
     if (s_cap < 1) s_cap = 1;
     if (s_cap > kMaxSplits) s_cap = kMaxSplits;
-    const int64_t s_need = ceil_div(cap * G, kStageFloats) + 1;   // a split's logits must fit the LDS staging
+    const int64_t s_need = ceil_div(cap * G, kStageFloats - 260 * G) + 1;   // a split's logits must fit the LDS staging
     if (s_need > kMaxSplits) return BUZZ_EUNSUPPORTED;
     if (s_cap < s_need) s_cap = s_need;
     L->s_cap = (int32_t)s_cap;
@@ -482,7 +482,7 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         if (S < 1) S = 1;
         if (S > L.s_cap) S = L.s_cap;
         int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
-        while (rps * L.G > kStageFloats) {                     // LDS staging bound; s_cap was sized for this
+        while ((rps + 4) * L.G > kStageFloats) {               // LDS staging bound (+ alignment slack); s_cap covers it
             S += 1;
             rps = ceil_div(ceil_div(n, S), tile) * tile;
         }
