@@ -27,7 +27,7 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 // Build-time tuning knobs (defaults are the measured best; a sweep overrides them with -D).
 #ifndef BUZZ_U_G1
-#define BUZZ_U_G1 8      // 16-byte loads of K (and of V) in flight per lane and trip, group size 1
+#define BUZZ_U_G1 4      // 16-byte loads of K (and of V) per lane and tile, group size 1 (two tiles in flight)
 #endif
 #ifndef BUZZ_U_G2
 #define BUZZ_U_G2 4
@@ -277,10 +277,26 @@ __global__ __launch_bounds__(256, BUZZ_MIN_BLOCKS) void attn_split_kernel(const 
         }
         const int per = ((cnt + NW - 1) / NW + WROWS - 1) / WROWS * WROWS;   // rows per wave, whole tiles
         const int w1 = min(cnt, (wave + 1) * per);
+        if constexpr (G == 1) {
+        // two tile buffers: the next tile's loads are issued before the current tile is consumed
+        u32x4 ka[U], va[U], kb[U], vb[U];
+        int base = wave * per;
+        if (base < w1) load_tile(ka, va, kp, vp, base, lead, cnt);
+        while (base < w1) {
+            if (base + WROWS < w1) load_tile(kb, vb, kp, vp, base + WROWS, lead, cnt);
+            compute_tile(ka, va, base, lead, cnt, lo - j0 + base - lead);
+            base += WROWS;
+            if (base >= w1) break;
+            if (base + WROWS < w1) load_tile(ka, va, kp, vp, base + WROWS, lead, cnt);
+            compute_tile(kb, vb, base, lead, cnt, lo - j0 + base - lead);
+            base += WROWS;
+        }
+        } else {
         for (int base = wave * per; base < w1; base += WROWS) {
             u32x4 kr[U], vr[U];
             load_tile(kr, vr, kp, vp, base, lead, cnt);
             compute_tile(kr, vr, base, lead, cnt, lo - j0 + base - lead);
+        }
         }
     }
 
