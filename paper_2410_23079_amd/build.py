@@ -9,7 +9,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbuzz.so")
-SOURCES = ["buzz_api.cpp", "attn_kernels.hip", "evict_kernels.hip", "prefill_kernels.hip"]
+# (source, object stem, extra defines); the attention kernels are one translation unit per dtype
+SOURCES = [("buzz_api.cpp", "buzz_api", []), ("evict_kernels.hip", "evict_kernels", []),
+           ("prefill_kernels.hip", "prefill_kernels", []),
+           ("attn_kernels.hip", "attn_fp32", ["-DBUZZ_TU=0"]), ("attn_kernels.hip", "attn_fp16", ["-DBUZZ_TU=1"]),
+           ("attn_kernels.hip", "attn_bf16", ["-DBUZZ_TU=2"]), ("attn_kernels.hip", "attn_common", ["-DBUZZ_TU=3"])]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
     # packed fp32 VALU forms are switched off for the whole library
@@ -25,9 +29,9 @@ def build(verbose: bool = False, extra_flags=(), out_path: str = LIB, obj_dir: s
     objs = []
     procs = []
     os.makedirs(obj_dir, exist_ok=True)
-    for src in SOURCES:
-        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
-        cmd = ["hipcc", "-x", "hip", *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+    for src, stem, defs in SOURCES:
+        obj = os.path.join(obj_dir, stem + ".o")
+        cmd = ["hipcc", "-x", "hip", *FLAGS, *defs, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
                "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)

@@ -476,9 +476,12 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         a.streaming = (cfg.flags & BUZZ_FLAG_STREAMING) ? 1
                       : (cfg.flags & BUZZ_FLAG_CACHED) ? 0 : (step_bytes > kLastLevelCacheBytes);
         const int tile = attn_tile_rows(cfg.kv_dtype, cfg.head_dim, L.G);
-        // few, long blocks amortise the per-block merge; a block count that fills every compute unit the same
-        // number of times avoids a tail: floor(2 * CUs / units) splits
-        int64_t S = c->user_splits > 0 ? c->user_splits : (int64_t)kBlocksPerCU * compute_units() / L.units;
+        // Few, long blocks amortise the per-block merge, and a block count that fills every compute unit the
+        // same number of times avoids a tail.  With at least one unit per compute unit a unit is ONE block
+        // (no merge across blocks at all), 8 waves wide while that still leaves every CU 8 waves; otherwise
+        // floor(2 * CUs / units) splits of 4 waves.
+        const int cus = compute_units();
+        int64_t S = c->user_splits > 0 ? c->user_splits : (L.units >= cus ? 1 : (int64_t)kBlocksPerCU * cus / L.units);
         if (S < 1) S = 1;
         if (S > L.s_cap) S = L.s_cap;
         int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
@@ -488,6 +491,7 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         }
         a.rows_per_split = (int32_t)rps;
         a.n_splits = (int32_t)ceil_div(n, rps);
+        a.waves = (a.n_splits == 1 && L.units < 2 * cus) ? 8 : 4;
         if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st, prof_pair(c, 0)))
             return hip_rc(e);
         if (c->prof) c->prof_row_bytes += (double)L.units * (double)n * 2.0 * L.row_bytes;

@@ -22,7 +22,7 @@
 namespace buzz {
 
 constexpr int kMaxSplits = 128;        // upper bound on key-range splits per unit
-constexpr int kBlocksPerCU = 2;        // automatic split choice: units * splits <= this many blocks per compute unit
+constexpr int kBlocksPerCU = 2;        // automatic split choice: units * splits <= this many 4-wave blocks per compute unit
 constexpr int kDefaultCUs = 256;       // MI355X; replaced by the device's own count at the first launch
 constexpr int kMaxBlocks = 4096;       // partial buffers are sized for units * splits <= this (or 1 split per unit)
 constexpr int kMaxSegment = 4096;
@@ -67,6 +67,7 @@ struct AttnArgs {
     int32_t n_splits;
     int32_t s_cap;
     int32_t Hq, Hkv;
+    int32_t waves;       // waves per block: 4, or 8 when every unit is a single split
     int32_t pending;     // 1: the previous step's score update has not been applied yet
     int32_t streaming;   // 1: K/V are read with the non-temporal hint (working set exceeds the last-level cache)
     float scale_log2;    // softmax scale * log2(e)
