@@ -477,11 +477,11 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
                       : (cfg.flags & BUZZ_FLAG_CACHED) ? 0 : (step_bytes > kLastLevelCacheBytes);
         const int tile = attn_tile_rows(cfg.kv_dtype, cfg.head_dim, L.G);
         // Few, long blocks amortise the per-block merge, and a block count that fills every compute unit the
-        // same number of times avoids a tail.  With at least one unit per compute unit a unit is ONE block
-        // (no merge across blocks at all), 8 waves wide while that still leaves every CU 8 waves; otherwise
-        // floor(2 * CUs / units) splits of 4 waves.
+        // same number of times avoids a tail.  Automatic choice: one block per compute unit, 8 waves wide
+        // (floor(CUs / units) splits); with at least one unit per CU a unit is a single block and nothing is
+        // merged across blocks at all.
         const int cus = compute_units();
-        int64_t S = c->user_splits > 0 ? c->user_splits : (L.units >= cus ? 1 : (int64_t)kBlocksPerCU * cus / L.units);
+        int64_t S = c->user_splits > 0 ? c->user_splits : (L.units >= cus ? 1 : cus / L.units);
         if (S < 1) S = 1;
         if (S > L.s_cap) S = L.s_cap;
         int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
@@ -491,7 +491,7 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         }
         a.rows_per_split = (int32_t)rps;
         a.n_splits = (int32_t)ceil_div(n, rps);
-        a.waves = (a.n_splits == 1 && L.units < 2 * cus) ? 8 : 4;
+        a.waves = (int64_t)L.units * a.n_splits <= cus ? 8 : 4;   // keep about 8 waves per compute unit
         if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st, prof_pair(c, 0)))
             return hip_rc(e);
         if (c->prof) c->prof_row_bytes += (double)L.units * (double)n * 2.0 * L.row_bytes;

@@ -22,7 +22,6 @@
 namespace buzz {
 
 constexpr int kMaxSplits = 128;        // upper bound on key-range splits per unit
-constexpr int kBlocksPerCU = 2;        // automatic split choice: units * splits <= this many 4-wave blocks per compute unit
 constexpr int kDefaultCUs = 256;       // MI355X; replaced by the device's own count at the first launch
 constexpr int kMaxBlocks = 4096;       // partial buffers are sized for units * splits <= this (or 1 split per unit)
 constexpr int kMaxSegment = 4096;
