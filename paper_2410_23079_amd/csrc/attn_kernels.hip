@@ -370,7 +370,6 @@ __global__ __launch_bounds__(NW * 64, BUZZ_MIN_BLOCKS) void attn_split_kernel(co
     constexpr int RPW = 64 / LPR;         // rows per wave-wide load
     constexpr int ROWB = D * (int)sizeof(T);
     constexpr int WROWS = RPW * U;        // rows one wave consumes per trip
-    constexpr int TILE = NW * WROWS;
     static_assert(LPR >= 8 && LPR <= 64, "row must span 8..64 lanes");
     static_assert((WROWS & (WROWS - 1)) == 0, "tiles anchor at multiples of WROWS");
 
@@ -406,9 +405,8 @@ __global__ __launch_bounds__(NW * 64, BUZZ_MIN_BLOCKS) void attn_split_kernel(co
     }
 
     // Work split inside a block.  A split's logical row range is cut into at most four physically
-    // contiguous runs; inside a run every wave owns one contiguous sub-range and walks it in tiles of
-    // WROWS rows on a grid anchored at a physical multiple of WROWS (`lead` rows before the run's first
-    // row are masked).  The streaming phase only reads: logits are staged in LDS, and all per-row side
+    // contiguous runs; inside a run the block's waves take tiles of WROWS rows round-robin, on a grid
+    // anchored at a physical multiple of WROWS (`lead` rows before the run's first row are masked).  The streaming phase only reads: logits are staged in LDS, and all per-row side
     // traffic (this step's logits out, the previous step's logits and the old score in, the new score out)
     // happens in one dense phase at the end of the block.  Writes that trickle into a saturated read
     // stream were measured to cost ~5% of the kernel per 1% of extra bytes.
@@ -486,24 +484,25 @@ __global__ __launch_bounds__(NW * 64, BUZZ_MIN_BLOCKS) void attn_split_kernel(co
                 if (c == 0) a.pos[ubase + a.new_phys] = a.new_pos;
             }
         }
-        const int per = ((cnt + NW - 1) / NW + WROWS - 1) / WROWS * WROWS;   // rows per wave, whole tiles
-        const int w1 = min(cnt, (wave + 1) * per);
+        // the block's waves take the run's tiles round-robin (a block-contiguous stream; measured ~5% faster
+        // than giving every wave its own contiguous piece)
+        constexpr int STEP = NW * WROWS;
         if constexpr (G == 1) {
         // two tile buffers: the next tile's loads are issued before the current tile is consumed
         u32x4 ka[U], va[U], kb[U], vb[U];
-        int base = wave * per;
-        if (base < w1) load_tile(ka, va, kp, vp, base, lead, cnt);
-        while (base < w1) {
-            if (base + WROWS < w1) load_tile(kb, vb, kp, vp, base + WROWS, lead, cnt);
+        int base = wave * WROWS;
+        if (base < cnt) load_tile(ka, va, kp, vp, base, lead, cnt);
+        while (base < cnt) {
+            if (base + STEP < cnt) load_tile(kb, vb, kp, vp, base + STEP, lead, cnt);
             compute_tile(ka, va, base, lead, cnt, lo - j0 + base - lead);
-            base += WROWS;
-            if (base >= w1) break;
-            if (base + WROWS < w1) load_tile(ka, va, kp, vp, base + WROWS, lead, cnt);
+            base += STEP;
+            if (base >= cnt) break;
+            if (base + STEP < cnt) load_tile(ka, va, kp, vp, base + STEP, lead, cnt);
             compute_tile(kb, vb, base, lead, cnt, lo - j0 + base - lead);
-            base += WROWS;
+            base += STEP;
         }
         } else {
-        for (int base = wave * per; base < w1; base += WROWS) {
+        for (int base = wave * WROWS; base < cnt; base += STEP) {
             u32x4 kr[U], vr[U];
             load_tile(kr, vr, kp, vp, base, lead, cnt);
             compute_tile(kr, vr, base, lead, cnt, lo - j0 + base - lead);
@@ -726,10 +725,8 @@ __global__ __launch_bounds__(NW * 64) void attn_split_mfma_kernel(const AttnArgs
                 if (tid == 0) a.pos[x.ubase + a.new_phys] = a.new_pos;
             }
         }
-        const int per = ((cnt + NW - 1) / NW + WROWS - 1) / WROWS * WROWS;   // rows per wave, whole tiles
-        const int w1 = min(cnt, (wave + 1) * per);
-        for (int base = wave * per; base < w1; base += WROWS) {   // (double-buffering was measured 4% slower here)
-            u32x4 kk[QP], vv[VS][4];
+        for (int base = wave * WROWS; base < cnt; base += NW * WROWS) {   // waves take tiles round-robin
+            u32x4 kk[QP], vv[VS][4];                      // (double-buffering was measured 4% slower here)
             load_tile(kk, vv, kp, vp, base, lead, cnt);
             compute_tile(kk, vv, base, lead, cnt, lo - j0 + base - lead);
         }
