@@ -173,7 +173,8 @@ def main():
             if t and layers == wl.layers and not args.splits:
                 traffic = {"fetch_bytes": t["fetch_bytes_per_launch"], "write_bytes": t["write_bytes_per_launch"],
                            "source": t["source"]}
-        roofline = {"bound": "hbm", "kernel": "attn_split_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        kname = "attn_split_mfma_kernel" if (wl.group > 1 and wl.dtype != "fp32") else "attn_split_kernel"
+        roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "avg_launch_us": attn_ms * 1e3 / max(launches, 1), "launches": launches,
                     "bytes_per_launch": algo_bytes / max(launches, 1), "traffic": traffic}
