@@ -55,7 +55,16 @@ enum {
        cache reads more than the GPU's 256 MB last-level cache, cached loads otherwise.  A caller that runs many
        layers (so that nothing survives in cache between two steps of one layer) should set STREAMING. */
     BUZZ_FLAG_STREAMING = 4u,
-    BUZZ_FLAG_CACHED = 8u
+    BUZZ_FLAG_CACHED = 8u,
+    /* Log-n scaled attention (Sec. 3.5): the softmax scale of a query is multiplied by log(n)/log(512),
+       n = number of tokens it sees, itself included (prompt queries: their position + 1; decode step: tokens
+       seen so far + 1).  The library tracks n. */
+    BUZZ_FLAG_LOG_N = 16u,
+    /* T bounds old + new tokens together instead of the new tokens alone: eviction fires when
+       n_old + new_count reaches T.  This is how the proof of the Parameter Estimation theorem reads T; meant
+       for old_stride > 1.  The old region then holds at most T rows, and a prefill keeps sampling until its
+       survivors fit T rows ("a container of length T + k + w", Remark 2) unless `capacity` says otherwise. */
+    BUZZ_FLAG_THRESHOLD_TOTAL = 32u
 };
 
 /* Symbols follow the paper's notation table (Sec. 3.3). */
@@ -197,6 +206,13 @@ int buzz_cache_profile_read(buzz_cache_t* cache, buzz_profile_t* out);
  * Errors: BUZZ_EINVAL, BUZZ_EHIP.
  */
 int buzz_bench_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+/*
+ * The eviction threshold the Parameter Estimation theorem (Sec. 3.4) recommends for stride s and window w
+ * under BUZZ_FLAG_THRESHOLD_TOTAL: T = w (s^2 + 1)/(s + 1) for odd s, w (s - 1) for even s, rounded to the
+ * nearest integer and at least 1.  Returns 0 for s < 1 or w < 0.  Pure host arithmetic.
+ */
+int64_t buzz_suggest_threshold(int32_t segment, int32_t window);
 
 /* Static description of a status code (host string, never NULL). */
 const char* buzz_strerror(int status);

@@ -37,7 +37,12 @@
  *     s^ = floor((s+1)/2) unless the caller overrides it (s^ = 1 keeps all);
  *   - in prefill the eviction runs once when the new count is >= T and, for
  *     s^ > 1, again while sink + old + window + T exceeds the capacity
- *     (Remark 2).
+ *     (Remark 2);
+ *   - optional variants: log-n scaled attention (Sec. 3.5) multiplies the
+ *     softmax scale by log(n)/log(512), n = number of tokens the query sees,
+ *     itself included; and the threshold may instead bound old + new tokens
+ *     together, which is how the proof of the Parameter Estimation theorem
+ *     reads T.
  */
 #include <math.h>
 #include <stdint.h>
@@ -53,7 +58,8 @@ typedef struct {
     int32_t evict_every; /* T  */
     int32_t old_stride;  /* s^ ; 0 => floor((s+1)/2) */
     int32_t auto_evict;  /* decode_step evicts by itself when the count reaches T */
-    int32_t reserved;
+    int32_t variant;     /* bit 0: log-n scaled attention (Sec. 3.5): scale *= log(n)/log(512), n = tokens so far
+                            bit 1: T bounds old + new tokens together (the reading used by the theorem's proof) */
     int64_t capacity;    /* logical row bound used by Remark 2; 0 => none */
     double  softmax_scale; /* 0 => 1/sqrt(head_dim) */
 } oracle_config;
@@ -79,9 +85,12 @@ static int64_t old_stride_of(const oracle_config *c)
     return c->old_stride > 0 ? c->old_stride : (c->segment + 1) / 2; /* Sec. 3.3, BeeHive */
 }
 
-static double scale_of(const oracle_config *c)
+/* softmax scale for a query that sees n_ctx tokens (itself included) */
+static double scale_of(const oracle_config *c, int64_t n_ctx)
 {
-    return c->softmax_scale != 0.0 ? c->softmax_scale : 1.0 / sqrt((double)c->head_dim); /* eq. 3 */
+    double s = c->softmax_scale != 0.0 ? c->softmax_scale : 1.0 / sqrt((double)c->head_dim); /* eq. 3 */
+    if (c->variant & 1) s *= log((double)n_ctx) / log(512.0);   /* Sec. 3.5: log_512(n) / sqrt(d) */
+    return s;
 }
 
 static int unit_reserve(unit_t *x, int64_t rows, int64_t D)
@@ -211,6 +220,13 @@ static int64_t new_count_of(const oracle_config *c, const unit_t *x)
     return v > 0 ? v : 0;
 }
 
+/* the quantity compared with T: buffered new tokens (Alg. 1), or old + new (proof of the theorem) */
+static int64_t trigger_count_of(const oracle_config *c, const unit_t *x)
+{
+    const int64_t nc = new_count_of(c, x);
+    return (c->variant & 2) ? x->n_old + nc : nc;
+}
+
 /* softmax(scale * q . K_j) over rows j < n of one unit; p has n entries */
 static void softmax_row(const double *q, const double *K, int64_t n, int64_t D, double scale, double *p)
 {
@@ -240,7 +256,6 @@ int oracle_prefill(oracle_t *o, const double *K, const double *V, int64_t N,
     if (!o || !K || !V || N < 0 || n_obs < 0 || n_obs > N || (n_obs > 0 && !q_obs)) return ORACLE_EINVAL;
     const oracle_config *c = &o->cfg;
     const int64_t D = c->head_dim, G = c->n_q_heads / c->n_kv_heads, Hkv = c->n_kv_heads, Hq = c->n_q_heads;
-    const double scale = scale_of(c);
     int rc = 0;
 #pragma omp parallel for schedule(dynamic)
     for (int64_t ui = 0; ui < o->n_units; ++ui) {
@@ -265,13 +280,13 @@ int oracle_prefill(oracle_t *o, const double *K, const double *V, int64_t N,
             const int64_t i = N - n_obs + t;               /* position of this query */
             for (int64_t g = 0; g < G; ++g) {
                 const double *q = q_obs + (((b * Hq) + h * G + g) * n_obs + t) * D;
-                softmax_row(q, x->K, i + 1, D, scale, p);  /* causal: keys 0..i */
+                softmax_row(q, x->K, i + 1, D, scale_of(c, i + 1), p);  /* causal: keys 0..i */
                 for (int64_t j = 0; j <= i; ++j) x->A[j] += p[j];
             }
         }
         free(p);
         /* Remark 2 */
-        if (new_count_of(c, x) >= c->evict_every) {
+        if (trigger_count_of(c, x) >= c->evict_every) {
             int r = unit_evict(c, x);
             if (r) {
 #pragma omp critical
@@ -304,7 +319,7 @@ int oracle_decode_step(oracle_t *o, const double *q, const double *k_new, const 
     if (!o || !q || !k_new || !v_new || !out) return ORACLE_EINVAL;
     const oracle_config *c = &o->cfg;
     const int64_t D = c->head_dim, G = c->n_q_heads / c->n_kv_heads, Hkv = c->n_kv_heads, Hq = c->n_q_heads;
-    const double scale = scale_of(c);
+    const double scale = scale_of(c, o->tokens_seen + 1);   /* the new token counts */
     int rc = 0;
 #pragma omp parallel for schedule(static)
     for (int64_t ui = 0; ui < o->n_units; ++ui) {
@@ -337,7 +352,7 @@ int oracle_decode_step(oracle_t *o, const double *q, const double *k_new, const 
             for (int64_t j = 0; j < x->n; ++j) x->A[j] += p[j];   /* accumulated score */
         }
         free(p);
-        if (c->auto_evict && new_count_of(c, x) >= c->evict_every) {  /* Alg. 1: buffer T, then sample */
+        if (c->auto_evict && trigger_count_of(c, x) >= c->evict_every) {  /* Alg. 1: buffer T, then sample */
             int r = unit_evict(c, x);
             if (r) {
 #pragma omp critical

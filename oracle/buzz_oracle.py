@@ -35,7 +35,7 @@ class _Cfg(ctypes.Structure):
         ("sink", ctypes.c_int32), ("window", ctypes.c_int32),
         ("segment", ctypes.c_int32), ("keep", ctypes.c_int32),
         ("evict_every", ctypes.c_int32), ("old_stride", ctypes.c_int32),
-        ("auto_evict", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("auto_evict", ctypes.c_int32), ("variant", ctypes.c_int32),
         ("capacity", ctypes.c_int64), ("softmax_scale", ctypes.c_double),
     ]
 
@@ -93,6 +93,8 @@ class OracleConfig:
     auto_evict: bool = True
     capacity: int = 0
     softmax_scale: float = 0.0
+    log_n: bool = False            # Sec. 3.5: scale *= log(n)/log(512)
+    threshold_total: bool = False  # T bounds old + new tokens (theorem proof's reading)
 
 
 class OracleCache:
@@ -102,7 +104,8 @@ class OracleCache:
         self.cfg = cfg
         self._lib = _load()
         c = _Cfg(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.sink, cfg.window,
-                 cfg.segment, cfg.keep, cfg.evict_every, cfg.old_stride, int(cfg.auto_evict), 0,
+                 cfg.segment, cfg.keep, cfg.evict_every, cfg.old_stride, int(cfg.auto_evict),
+                 int(cfg.log_n) | (int(cfg.threshold_total) << 1),
                  cfg.capacity, cfg.softmax_scale)
         h = ctypes.c_void_p()
         _chk(self._lib.oracle_create(ctypes.byref(c), ctypes.byref(h)), "oracle_create")

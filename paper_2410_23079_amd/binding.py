@@ -18,11 +18,13 @@ FLAG_AUTO_EVICT = 1
 FLAG_DRY_RUN = 2
 FLAG_STREAMING = 4
 FLAG_CACHED = 8
+FLAG_LOG_N = 16
+FLAG_THRESHOLD_TOTAL = 32
 DTYPE_CODES = {"fp32": 0, "fp16": 1, "bf16": 2}
 
 EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step", "buzz_evict",
            "buzz_cache_destroy", "buzz_cache_len", "buzz_cache_export", "buzz_cache_set_splits", "buzz_cache_profile",
-           "buzz_cache_profile_read", "buzz_bench_copy", "buzz_strerror"]
+           "buzz_cache_profile_read", "buzz_bench_copy", "buzz_suggest_threshold", "buzz_strerror"]
 
 
 class BuzzError(RuntimeError):
@@ -101,6 +103,8 @@ def load_library():
     lib.buzz_cache_profile.argtypes = [P, ctypes.c_int]
     lib.buzz_cache_profile_read.argtypes = [P, ctypes.POINTER(_Profile)]
     lib.buzz_bench_copy.argtypes = [P, P, ctypes.c_size_t, P]
+    lib.buzz_suggest_threshold.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.buzz_suggest_threshold.restype = ctypes.c_int64
     lib.buzz_strerror.argtypes = [ctypes.c_int]
     lib.buzz_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -117,6 +121,11 @@ def workspace_bytes(cfg: BuzzConfig) -> int:
     c = cfg.to_c()
     _check(load_library().buzz_workspace_bytes(ctypes.byref(c), ctypes.byref(out)), "buzz_workspace_bytes")
     return out.value
+
+
+def suggest_threshold(segment: int, window: int) -> int:
+    """Eviction threshold recommended by the Parameter Estimation theorem (Sec. 3.4) for FLAG_THRESHOLD_TOTAL."""
+    return load_library().buzz_suggest_threshold(segment, window)
 
 
 def bench_copy(dst, src, stream=None):

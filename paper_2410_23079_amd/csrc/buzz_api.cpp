@@ -30,7 +30,8 @@ int make_layout(const buzz_config_t* c, Layout* L)
     if (c->kv_dtype < BUZZ_FP32 || c->kv_dtype > BUZZ_BF16) return BUZZ_EINVAL;
     if (c->sink < 0 || c->window < 0 || c->segment < 1 || c->keep < 0 || c->evict_every < 1) return BUZZ_EINVAL;
     if (c->old_stride < 0 || c->max_context < 1 || c->capacity < 0 || c->reserved != 0) return BUZZ_EINVAL;
-    if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN | BUZZ_FLAG_STREAMING | BUZZ_FLAG_CACHED))
+    if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN | BUZZ_FLAG_STREAMING | BUZZ_FLAG_CACHED |
+                              BUZZ_FLAG_LOG_N | BUZZ_FLAG_THRESHOLD_TOTAL))
         return BUZZ_EINVAL;
     if ((c->flags & BUZZ_FLAG_STREAMING) && (c->flags & BUZZ_FLAG_CACHED)) return BUZZ_EINVAL;
     if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BUZZ_EINVAL;
@@ -48,6 +49,8 @@ int make_layout(const buzz_config_t* c, Layout* L)
     if (c->capacity > 0) {
         old_cap = c->capacity - k - w - T;
         if (old_cap < 0) return BUZZ_EINVAL;
+    } else if (c->flags & BUZZ_FLAG_THRESHOLD_TOTAL) {
+        old_cap = keep == 0 ? 0 : T;                            // old + new never exceed T
     } else {
         const int64_t bound = keep * (ceil_div(M, s) + ceil_div(M, T) + 1);
         old_cap = keep == 0 ? 0 : (bound < M ? bound : M);
@@ -130,6 +133,14 @@ struct buzz_cache {
     {
         const int64_t v = n() - cfg.sink - n_old - cfg.window;
         return v > 0 ? v : 0;
+    }
+    int64_t trigger_count() const                               // what is compared with T
+    {
+        return (cfg.flags & BUZZ_FLAG_THRESHOLD_TOTAL) ? n_old + new_count() : new_count();
+    }
+    double log_n_factor(int64_t n_ctx) const                    // Sec. 3.5: log_512(n) for a query that sees n tokens
+    {
+        return (cfg.flags & BUZZ_FLAG_LOG_N) ? log((double)n_ctx) / log(512.0) : 1.0;
     }
     RingMap map() const
     {
@@ -357,7 +368,7 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
     if (sample) {
         const int64_t last = M % s < keep ? M % s : keep;
         survivors = keep * (M / s) + last;
-        if (L.old_stride > 1 && cfg.capacity > 0) {            // Remark 2: keep sampling until it fits
+        if (L.old_stride > 1 && (cfg.capacity > 0 || (cfg.flags & BUZZ_FLAG_THRESHOLD_TOTAL))) {   // Remark 2: sample until it fits
             while (survivors > L.old_cap) {
                 const int64_t nxt = ceil_div(survivors, L.old_stride);
                 if (nxt >= survivors) return BUZZ_ECAPACITY;
@@ -386,6 +397,7 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
                 oa.t_begin = (int32_t)t0; oa.t_count = (int32_t)((n_obs - t0) < max_q ? (n_obs - t0) : max_q);
                 oa.Hq = cfg.n_q_heads; oa.Hkv = cfg.n_kv_heads;
                 oa.scale_log2 = c->scale * 1.4426950408889634f;
+                oa.log_n = (cfg.flags & BUZZ_FLAG_LOG_N) ? 1 : 0;
                 if (hipError_t e = launch_obs_scores(cfg.kv_dtype, cfg.head_dim, G, oa, L.units, st)) return hip_rc(e);
             }
         }
@@ -471,7 +483,7 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         a.cap = L.cap;
         a.Hq = cfg.n_q_heads; a.Hkv = cfg.n_kv_heads;
         a.s_cap = L.s_cap;
-        a.scale_log2 = c->scale * 1.4426950408889634f;
+        a.scale_log2 = (float)(c->scale * 1.4426950408889634 * c->log_n_factor(c->tokens_seen + 1));
         const double step_bytes = (double)L.units * (double)n * 2.0 * L.row_bytes;
         a.streaming = (cfg.flags & BUZZ_FLAG_STREAMING) ? 1
                       : (cfg.flags & BUZZ_FLAG_CACHED) ? 0 : (step_bytes > kLastLevelCacheBytes);
@@ -501,7 +513,7 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
     c->sink_filled = sink_filled;
     c->tail = tail;
     c->tokens_seen += 1;
-    if ((cfg.flags & BUZZ_FLAG_AUTO_EVICT) && c->new_count() >= cfg.evict_every) return evict_impl(c, st);
+    if ((cfg.flags & BUZZ_FLAG_AUTO_EVICT) && c->trigger_count() >= cfg.evict_every) return evict_impl(c, st);
     return BUZZ_OK;
 }
 
@@ -559,6 +571,15 @@ int buzz_bench_copy(void* dst, const void* src, size_t bytes, void* hip_stream)
 {
     if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return BUZZ_EINVAL;
     return hip_rc(launch_plain_copy(dst, src, bytes, (hipStream_t)hip_stream));
+}
+
+int64_t buzz_suggest_threshold(int32_t segment, int32_t window)
+{
+    if (segment < 1 || window < 0) return 0;
+    const double s = segment, w = window;
+    const double t = (segment & 1) ? w * (s * s + 1.0) / (s + 1.0) : w * (s - 1.0);
+    const int64_t r = (int64_t)floor(t + 0.5);
+    return r < 1 ? 1 : r;
 }
 
 const char* buzz_strerror(int status)

@@ -105,6 +105,7 @@ struct ObsArgs {               // prefill scoring: causal attention of observed 
     int32_t N, n_obs;
     int32_t t_begin, t_count;  // queries scored by this pass; t_count * G <= kObsRows
     int32_t Hq, Hkv;
+    int32_t log_n;             // 1: a query at prompt position i is scaled by log(i + 1) / log(512) (Sec. 3.5)
     float scale_log2;
 };
 

@@ -33,21 +33,29 @@ template <> __device__ inline void cvt16B<BUZZ_FP16>(const uint4& r, float* f) {
     for (int i = 0; i < 4; ++i) { const half2_t h = __builtin_bit_cast(half2_t, w[i]); f[2 * i] = (float)h.x; f[2 * i + 1] = (float)h.y; }
 }
 
+// softmax scale (log2 units) of the query at prompt position `pos`; Sec. 3.5 multiplies it by log_512(pos + 1)
+__device__ inline float query_scale(const ObsArgs& a, int pos)
+{
+    return a.log_n ? a.scale_log2 * (logf((float)(pos + 1)) * (1.0f / 6.2383246250395077f)) : a.scale_log2;
+}
+
 template <int DT> struct Vec { static constexpr int N = DT == BUZZ_FP32 ? 4 : 8; };
 
 constexpr int kTile = 32;   // rows staged in LDS per trip
 
 // cooperative load of `rows` rows of D elements (row r at src + row_off(r)) into fp32 LDS [kTile][D]
-template <int DT, int D, typename RowPtr>
-__device__ inline void stage_rows(float* lds, int rows, float scale, RowPtr row_ptr)
+template <int DT, int D, typename RowPtr, typename RowScale>
+__device__ inline void stage_rows(float* lds, int rows, RowScale row_scale, RowPtr row_ptr)
 {
     constexpr int VEC = Vec<DT>::N, CH = D / VEC;         // 16-byte chunks per row
     for (int i = threadIdx.x; i < kTile * CH; i += 256) {
         const int r = i / CH, ch = i - r * CH;
         float f[VEC];
+        float scale = 0.f;
         if (r < rows) {
             const uint4 raw = *(const uint4*)(row_ptr(r) + (size_t)ch * 16);
             cvt16B<DT>(raw, f);
+            scale = row_scale(r);
         } else {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) f[v] = 0.f;
@@ -83,6 +91,7 @@ __global__ __launch_bounds__(256) void obs_row_stats_kernel(const ObsArgs a)
     const bool live = r < R;
     const int t = a.t_begin + (live ? r / G : 0), g = live ? r % G : 0;
     const int limit = a.N - a.n_obs + t;                       // last key this query may see
+    const float qscale = query_scale(a, limit);
     float qreg[D];
     {
         const char* qp = (const char*)a.q_obs + ((size_t)(b * a.Hq + kvh * G + g) * a.n_obs + t) * ROWB;
@@ -91,7 +100,7 @@ __global__ __launch_bounds__(256) void obs_row_stats_kernel(const ObsArgs a)
             float f[VEC];
             cvt16B<DT>(*(const uint4*)(qp + ch * 16), f);
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) qreg[ch * VEC + v] = f[v] * a.scale_log2;
+            for (int v = 0; v < VEC; ++v) qreg[ch * VEC + v] = f[v] * qscale;
         }
     }
     const int kbeg = kb * kObsKeyBlock, kend = min(a.N, kbeg + kObsKeyBlock);
@@ -100,7 +109,7 @@ __global__ __launch_bounds__(256) void obs_row_stats_kernel(const ObsArgs a)
     for (int k0 = kbeg; k0 < kend; k0 += kTile) {
         const int rows = min(kTile, kend - k0);
         __syncthreads();
-        stage_rows<DT, D>(tile, rows, 1.0f, [&](int rr) { return Kb + (size_t)(k0 + rr) * ROWB; });
+        stage_rows<DT, D>(tile, rows, [](int) { return 1.0f; }, [&](int rr) { return Kb + (size_t)(k0 + rr) * ROWB; });
         __syncthreads();
 #pragma unroll 2
         for (int kk = 0; kk < rows; ++kk) {
@@ -155,10 +164,12 @@ __global__ __launch_bounds__(256) void obs_col_sums_kernel(const ObsArgs a, cons
     for (int r0 = 0; r0 < R; r0 += kTile) {
         const int rows = min(kTile, R - r0);
         __syncthreads();
-        stage_rows<DT, D>(tile, rows, a.scale_log2, [&](int rr) {
-            const int r = r0 + rr, t = a.t_begin + r / G, g = r % G;
-            return (const char*)a.q_obs + ((size_t)(b * a.Hq + kvh * G + g) * a.n_obs + t) * ROWB;
-        });
+        stage_rows<DT, D>(tile, rows,
+                          [&](int rr) { return query_scale(a, a.N - a.n_obs + a.t_begin + (r0 + rr) / G); },
+                          [&](int rr) {
+                              const int r = r0 + rr, t = a.t_begin + r / G, g = r % G;
+                              return (const char*)a.q_obs + ((size_t)(b * a.Hq + kvh * G + g) * a.n_obs + t) * ROWB;
+                          });
         __syncthreads();
 #pragma unroll 4
         for (int rr = 0; rr < kTile; ++rr) {

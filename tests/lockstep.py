@@ -15,7 +15,7 @@ import numpy as np
 import torch
 
 from oracle.buzz_oracle import OracleCache, OracleConfig
-from paper_2410_23079_amd import FLAG_AUTO_EVICT, BuzzCache, BuzzConfig
+from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_LOG_N, FLAG_THRESHOLD_TOTAL, BuzzCache, BuzzConfig
 from workloads import Workload
 
 OUT_TOL = 2e-3      # contract: max |o - o_ref| / max |o_ref| per (batch, head) vector
@@ -60,10 +60,10 @@ def score_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float((np.abs(got - ref) / np.maximum(1.0, np.abs(ref))).max())
 
 
-def gpu_prompt_scores(wl: Workload, prompt, n_obs: int):
+def gpu_prompt_scores(wl: Workload, prompt, n_obs: int, flags: int = 0):
     """Prompt scores from the library's own prefill scoring, with a window so large nothing is evicted."""
     N = prompt["K"].shape[2]
-    cfg = buzz_config(wl, max_context=N + 1, sink=0, window=N + 1, keep=1, old_stride=1)
+    cfg = buzz_config(wl, flags=flags, max_context=N + 1, sink=0, window=N + 1, keep=1, old_stride=1)
     c = BuzzCache(cfg)
     q_obs = prompt["q_obs"][:, :, prompt["q_obs"].shape[2] - n_obs:, :].contiguous() if n_obs else None
     c.prefill(prompt["K"], prompt["V"], q_obs=q_obs)
@@ -74,7 +74,7 @@ def gpu_prompt_scores(wl: Workload, prompt, n_obs: int):
 
 
 def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=None, splits=0,
-                 check_auto=True, capacity=0):
+                 check_auto=True, capacity=0, log_n=False, threshold_total=False):
     """Returns a dict of the worst errors seen; raises AssertionError on any parity failure."""
     G, D = wl.group, wl.head_dim
     N = prompt["K"].shape[2]
@@ -86,29 +86,31 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
     uidx_b = torch.tensor([b for b, _ in units])
     uidx_h = torch.tensor([h for _, h in units])
     stats = dict(out=0.0, score=0.0, prefill_score=0.0, evictions=0)
+    vflags = (FLAG_LOG_N if log_n else 0) | (FLAG_THRESHOLD_TOTAL if threshold_total else 0)
+    okw = dict(log_n=log_n, threshold_total=threshold_total)
 
     # ---- prompt scores: library vs oracle, then shared
     Kp, Vp = unit_slices(prompt["K"], units, 1), unit_slices(prompt["V"], units, 1)
-    o_probe = OracleCache(oracle_config(wl, U, sink=0, window=N + 1, old_stride=1))
+    o_probe = OracleCache(oracle_config(wl, U, sink=0, window=N + 1, old_stride=1, log_n=log_n))
     q_obs_u = unit_slices(prompt["q_obs"][:, :, prompt["q_obs"].shape[2] - n_obs:, :], units, G) if n_obs else None
     o_probe.prefill(Kp, Vp, q_obs=q_obs_u)
     ref_ps = o_probe.export()[2][:, 0]                                   # [U,N]
-    ps = gpu_prompt_scores(wl, prompt, n_obs)                            # [B,Hkv,N] fp32 on GPU
+    ps = gpu_prompt_scores(wl, prompt, n_obs, FLAG_LOG_N if log_n else 0)   # [B,Hkv,N] fp32 on GPU
     got_ps = ps[uidx_b, uidx_h].double().cpu().numpy()
     err = score_err(got_ps, ref_ps)
     stats["prefill_score"] = err
     assert err <= SCORE_TOL, f"prefill scores off by {err}"
 
     # ---- both sides start from the same fp32 prompt scores
-    gpu = BuzzCache(buzz_config(wl, flags=0, max_context=N + steps, capacity=capacity))
+    gpu = BuzzCache(buzz_config(wl, flags=vflags, max_context=N + steps, capacity=capacity))
     if splits:
         gpu.set_splits(splits)
     gpu.prefill(prompt["K"], prompt["V"], init_score=ps)
-    ora = OracleCache(oracle_config(wl, U, capacity=capacity))
+    ora = OracleCache(oracle_config(wl, U, capacity=capacity, **okw))
     ora.prefill(Kp, Vp, init_score=got_ps[:, None, :])
     auto = None
     if check_auto:
-        auto = BuzzCache(buzz_config(wl, flags=FLAG_AUTO_EVICT, max_context=N + steps, capacity=capacity))
+        auto = BuzzCache(buzz_config(wl, flags=FLAG_AUTO_EVICT | vflags, max_context=N + steps, capacity=capacity))
         if splits:
             auto.set_splits(splits)
         q_obs = prompt["q_obs"][:, :, prompt["q_obs"].shape[2] - n_obs:, :].contiguous() if n_obs else None
@@ -144,7 +146,8 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
         if auto is not None:
             auto.decode_step(q, k, v, out_auto)
             assert torch.equal(out, out_auto), f"step {t}: auto-evict cache diverged from the manual one"
-        if gpu.lengths()[2] >= T:
+        _, n_old_now, new_now = gpu.lengths()
+        if (n_old_now + new_now if threshold_total else new_now) >= T:
             sg = compare_state(f"step {t} before eviction")
             ora.set_scores(sg[:, None, :])                                 # selection runs on the GPU's fp32 scores
             gpu.evict()

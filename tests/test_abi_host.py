@@ -178,3 +178,35 @@ def test_explicit_capacity_and_remark2_resampling():
     with pytest.raises(BuzzError) as e:
         g2.prefill(None, None, n_prompt=512)
     assert e.value.code == -2
+
+
+def test_theorem_threshold_helper():
+    from paper_2410_23079_amd import suggest_threshold
+    assert suggest_threshold(5, 1024) == round(1024 * 26 / 6)      # (s^2+1)/(s+1) = 4.33 for s = 5
+    assert suggest_threshold(4, 1024) == 3 * 1024                  # s - 1 for even s
+    assert suggest_threshold(1, 10) == 10 and suggest_threshold(0, 10) == 0 and suggest_threshold(3, 0) == 1
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_total_threshold_sizes_match_oracle(seed):
+    from paper_2410_23079_amd import FLAG_THRESHOLD_TOTAL
+    r = np.random.default_rng(50 + seed)
+    k, w = int(r.integers(0, 5)), int(r.integers(1, 30))
+    s, keep = int(r.integers(2, 9)), int(r.integers(1, 3))
+    T = int(r.integers(20, 120))
+    N, steps = int(r.integers(0, 600)), 300
+    sh = (s + 1) // 2
+    cap = k + w + 2 * T
+    g = BuzzCache(cfg(sink=k, window=w, segment=s, keep=keep, evict_every=T, old_stride=0, max_context=N + steps,
+                      flags=DRY | FLAG_THRESHOLD_TOTAL))
+    o = OracleCache(OracleConfig(1, 1, 1, 2, sink=k, window=w, segment=s, keep=keep, evict_every=T, old_stride=0,
+                                 threshold_total=True, capacity=cap))
+    g.prefill(None, None, n_prompt=N)
+    o.prefill(np.zeros((1, 1, N, 2)), np.zeros((1, 1, N, 2)))
+    assert g.lengths() == o.lengths()
+    z = np.zeros((1, 1, 2))
+    for _ in range(steps):
+        g.decode_step(None, None, None, None)
+        o.decode_step(z, z, z)
+        assert g.lengths() == o.lengths()
+        assert g.lengths()[1] <= T

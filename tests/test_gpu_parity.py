@@ -147,6 +147,28 @@ def test_log_n_scale_argument():
         assert ls.rel_err(ls.unit_slices(out, units, 1), ref) <= ls.OUT_EXPECT
 
 
+# ------------------------------------------------------------------ variants named by the paper
+def test_log_n_scaled_attention_tracks_context_length():
+    """Sec. 3.5: scale = log_512(n)/sqrt(d) with n = tokens the query sees, prompt scoring included."""
+    run(small(prompt=480, decode_steps=64, n_obs=24), log_n=True)          # crosses n = 512
+
+
+def test_log_n_with_grouped_queries():
+    run(small(batch=1, n_kv_heads=2, n_q_heads=8, head_dim=128, dtype="bf16", prompt=600, decode_steps=40,
+              sink=4, window=64, segment=16, keep=2, evict_every=16, n_obs=20), log_n=True)
+
+
+def test_threshold_bounds_old_plus_new_with_theorem_parameters():
+    """The proof's reading of T, with T from the Parameter Estimation theorem (s = 5: T/w = 4.33)."""
+    from paper_2410_23079_amd import suggest_threshold
+    w, s = 24, 5
+    T = suggest_threshold(s, w)
+    assert T == round(w * 26 / 6)
+    wl = small(prompt=400, decode_steps=260, sink=2, window=w, segment=s, keep=1, evict_every=T, old_stride=0, n_obs=16)
+    st = run(wl, threshold_total=True, capacity=wl.sink + w + 2 * T)
+    assert st["evictions"] >= 3
+
+
 # ------------------------------------------------------------------ full-size configs, sampled units
 def sampled_units(wl, count, seed):
     r = np.random.default_rng(seed)

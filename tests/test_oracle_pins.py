@@ -415,3 +415,64 @@ def test_planted_heavy_keys_survive():
     n, n_old, _ = o.lengths()
     assert n <= wl.sink + wl.window + wl.evict_every + n_old
     assert n_old == -(-(256 - 4 - 64) // 16) + 32 // 16
+
+
+# ---------------------------------------------------------------- variants: log-n scaling (Sec. 3.5) and the proof's threshold
+def test_log_n_scale_follows_context_length_and_is_plain_attention_at_512():
+    B, Hq, Hkv, D, N, steps = 1, 2, 1, 8, 508, 8
+    x = make(B, Hq, Hkv, D, N, steps, 21)
+    o = OracleCache(OracleConfig(B, Hq, Hkv, D, sink=4, window=10 ** 6, segment=4, log_n=True))
+    plain = OracleCache(OracleConfig(B, Hq, Hkv, D, sink=4, window=10 ** 6, segment=4))
+    o.prefill(x["K"], x["V"])
+    plain.prefill(x["K"], x["V"])
+    Kall, Vall = x["K"].copy(), x["V"].copy()
+    for t in range(steps):
+        out = o.decode_step(x["q"][t], x["k"][t], x["v"][t])
+        ref_plain = plain.decode_step(x["q"][t], x["k"][t], x["v"][t])
+        Kall = np.concatenate([Kall, x["k"][t][:, :, None, :]], axis=2)
+        Vall = np.concatenate([Vall, x["v"][t][:, :, None, :]], axis=2)
+        n = N + t + 1
+        ref = sdpa64(x["q"][t][0], np.repeat(Kall[0], 2, axis=0), np.repeat(Vall[0], 2, axis=0),
+                     scale=math.log(n) / math.log(512) / math.sqrt(D))
+        np.testing.assert_allclose(out[0], ref, rtol=1e-12, atol=1e-13)
+        if n == 512:                                     # "degrades to the traditional attention formula"
+            np.testing.assert_allclose(out, ref_plain, rtol=1e-12, atol=1e-13)
+        else:
+            assert np.abs(out - ref_plain).max() > 1e-9
+
+
+def test_log_n_prefill_scores_use_each_query_position():
+    B, Hq, Hkv, D, N, n_obs = 1, 1, 1, 8, 30, 6
+    x = make(B, Hq, Hkv, D, N, 0, 22)
+    o = OracleCache(OracleConfig(B, Hq, Hkv, D, sink=2, window=1000, segment=4, log_n=True))
+    o.prefill(x["K"], x["V"], q_obs=x["q_obs"][:, :, N - n_obs:, :])
+    A = o.export()[2][0, 0]
+    expect = np.zeros(N)
+    for t in range(n_obs):
+        i = N - n_obs + t
+        logits = torch.from_numpy(x["q_obs"][0, 0, i] @ x["K"][0, 0, :i + 1].T) * (math.log(i + 1) / math.log(512) / math.sqrt(D))
+        expect[:i + 1] += torch.softmax(logits, dim=-1).numpy()
+    np.testing.assert_allclose(A, expect, rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("s", [3, 5, 6])
+def test_total_threshold_runs_the_proofs_recurrence_by_itself(s):
+    """With T bounding old + new, automatic eviction reproduces a' = ceil(a/s^) + ceil((T-a)/s)."""
+    k, w, D, T = 2, 3, 1, 600
+    sh = (s + 1) // 2
+    o = OracleCache(OracleConfig(1, 1, 1, D, sink=k, window=w, segment=s, keep=1, evict_every=T, old_stride=0,
+                                 threshold_total=True))
+    o.prefill(np.zeros((1, 1, k + w, D)), np.zeros((1, 1, k + w, D)))
+    z = np.zeros((1, 1, D))
+    a, seen = 0, []
+    for _ in range(12 * T):
+        before = o.lengths()
+        o.decode_step(z, z, z)
+        after = o.lengths()
+        if after[2] == 0 and before[2] > 0:              # the buffered tokens were just consumed
+            a = -(-a // sh) + -(-(T - a) // s)
+            assert after[1] == a
+            seen.append(a)
+    assert len(seen) >= 8
+    predicted = (s * s + 1) / (s + 1) if s % 2 else (s - 1)
+    assert abs(T / seen[-1] - predicted) / predicted < 0.03
