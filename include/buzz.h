@@ -64,7 +64,12 @@ enum {
        n_old + new_count reaches T.  This is how the proof of the Parameter Estimation theorem reads T; meant
        for old_stride > 1.  The old region then holds at most T rows, and a prefill keeps sampling until its
        survivors fit T rows ("a container of length T + k + w", Remark 2) unless `capacity` says otherwise. */
-    BUZZ_FLAG_THRESHOLD_TOTAL = 32u
+    BUZZ_FLAG_THRESHOLD_TOTAL = 32u,
+    /* Bitwise reproducible decode steps.  By default the waves of a decode block claim their next tile of
+       cache rows from a shared counter, so which wave sums which rows depends on timing and the outputs and
+       scores of two identical runs may differ in the last bits (always within the stated tolerances).  With
+       this flag the assignment is fixed; measured cost: up to 5% of the step. */
+    BUZZ_FLAG_DETERMINISTIC = 64u
 };
 
 /* Symbols follow the paper's notation table (Sec. 3.3). */

@@ -46,8 +46,22 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 #ifndef BUZZ_U_G8
 #define BUZZ_U_G8 2
 #endif
+#ifndef BUZZ_MFMA_TR
+#define BUZZ_MFMA_TR 1   // 16-row tiles a wave of the matrix-core kernel has in flight
+#endif
 #ifndef BUZZ_MIN_BLOCKS
 #define BUZZ_MIN_BLOCKS 1  // second argument of __launch_bounds__
+#endif
+
+// Optional in-kernel time stamps (a tuning aid, compiled out unless BUZZ_TRACE is defined): slot s of
+// block b holds the wall clock (100 MHz) at which the block passed point s of the last launch.
+#if defined(BUZZ_TRACE) && BUZZ_TU == 2
+__device__ unsigned long long g_trace[kMaxBlocks * 16];
+#define BUZZ_STAMP(slot) do { g_trace[(size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
+#define BUZZ_STAMP_VALUE(slot, v) do { g_trace[(size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = (v); } while (0)
+#else
+#define BUZZ_STAMP(slot) do { } while (0)
+#define BUZZ_STAMP_VALUE(slot, v) do { } while (0)
 #endif
 
 template <typename T> struct Elem;
@@ -165,16 +179,130 @@ __device__ inline void run_bounds(const AttnArgs& a, const SplitCtx& x, int run,
 
 // Everything a block does once its waves have put their (max, sum, unnormalised output) into LDS.
 // The order hides as much latency as it can behind work that does not depend on it:
-//   1. request what the side phase needs (previous logits, old scores) -- nothing is waiting for it yet;
 //   2. merge the waves, publish the split's partial (write-through stores);
-//   3. side phase: this step's logits leave LDS, the previous step's score update is applied;
-//   4. wait for the published stores, synchronise, take the ticket;
-//   5. the block that drew the last ticket merges all splits with ONE round of device-scope loads.
-// sm_ml is scratch for step 5: [2][kMaxSplits][G] floats.
+//   3. wait for the published stores, synchronise, take the ticket;
+//   4. the block that drew the last ticket requests the partials (upper half of its waves);
+//   5. side phase: this step's logits leave LDS, the previous step's score update is applied
+//      (off the critical path: in the last block it runs under the latency of step 4's loads);
+//   6. the last block merges the splits and writes the output.
+// The tiles of a split, numbered across its (up to three) stored runs.  Inside a run tiles sit on a grid
+// anchored at a physical multiple of WROWS: `lead` rows before the run's first row are masked, `cnt` is
+// the run length measured from the anchor.  A block's waves do not own fixed tiles: apart from the first
+// one each, a wave claims its next tile from a counter in LDS when it has issued the loads of the current
+// one.  (With fixed round-robin tiles the waves launched first -- which the memory pipeline serves first
+// -- ended 15% earlier than the others, and the block waited for the slowest.)
+template <int WROWS>
+struct TileMap {
+    int lo0, lo1, lo2, ph0, ph1, ph2, ld0, ld1, ld2, c0, c1, c2, f1, f2, n_tiles;
+    __device__ inline TileMap(const AttnArgs& a, const SplitCtx& x)
+    {
+        int h;
+        run_bounds(a, x, 0, lo0, h, ph0); ld0 = ph0 & (WROWS - 1); c0 = h > lo0 ? h - lo0 + ld0 : 0;
+        run_bounds(a, x, 1, lo1, h, ph1); ld1 = ph1 & (WROWS - 1); c1 = h > lo1 ? h - lo1 + ld1 : 0;
+        run_bounds(a, x, 2, lo2, h, ph2); ld2 = ph2 & (WROWS - 1); c2 = h > lo2 ? h - lo2 + ld2 : 0;
+        f1 = (c0 + WROWS - 1) / WROWS;
+        f2 = f1 + (c1 + WROWS - 1) / WROWS;
+        n_tiles = f2 + (c2 + WROWS - 1) / WROWS;
+    }
+    __device__ inline int total() const { return n_tiles; }
+    // tile t -> its run's (lo, phys0, lead, cnt) and the tile's first row measured from the anchor
+    __device__ inline void locate(int t, int& l, int& p, int& ld, int& c, int& base) const
+    {
+        // (sums of "difference or 0" rather than nested selects between members: the latter turn into
+        // an indexed read of the structure and push it into private memory)
+        const bool r1 = t >= f1, r2 = t >= f2;
+        l = lo0 + (r1 ? lo1 - lo0 : 0) + (r2 ? lo2 - lo1 : 0);
+        p = ph0 + (r1 ? ph1 - ph0 : 0) + (r2 ? ph2 - ph1 : 0);
+        ld = ld0 + (r1 ? ld1 - ld0 : 0) + (r2 ? ld2 - ld1 : 0);
+        c = c0 + (r1 ? c1 - c0 : 0) + (r2 ? c2 - c1 : 0);
+        base = (t - (r1 ? f1 : 0) - (r2 ? f2 - f1 : 0)) * WROWS;
+    }
+};
+
+__device__ inline int claim_tile(int* counter)
+{
+    int t = 0;
+    if ((threadIdx.x & 63) == 0) t = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return __builtin_amdgcn_readfirstlane(t);
+}
+
+// The tile a wave takes after tile `last`: claimed from the block's counter, or -- when the caller asked
+// for results that do not depend on timing -- the next one of a fixed round-robin over `nw` waves.
+__device__ inline int next_tile(const AttnArgs& a, int* counter, int last, int nw)
+{
+    return a.fixed_tiles ? last + nw : claim_tile(counter);
+}
+
+// The previous step's softmax statistics of one unit (global maximum and 1/sum per head), which turn its
+// stored logits into probabilities.  A kernel requests them when it starts: they come from memory, and a
+// request made where they are needed would stall the end of the block for a full round trip.
+template <int G> struct PrevStat { float M[G], iL[G]; };
+
+template <int G>
+__device__ inline PrevStat<G> load_prev_stat(const AttnArgs& a, int unit)
+{
+    PrevStat<G> p;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        p.M[g] = a.pending ? a.stat_prev[((size_t)unit * G + g) * 2] : 0.f;
+        p.iL[g] = a.pending ? a.stat_prev[((size_t)unit * G + g) * 2 + 1] : 0.f;
+    }
+    return p;
+}
+
+// What a thread needs for the first pass of its side phase (4 consecutive physical rows in each stored
+// run of the split): the old scores and the previous step's logits.  Requested when the kernel starts and
+// consumed after the streaming loop, so that their latency is never exposed.
+// (They occupy 12 (G + 1) registers through the whole streaming loop; where that would spill -- 8 heads
+// per row, or 4 heads of 256 columns -- the request is made after the loop instead.)
+template <int G> struct SideRows { float4 sc[3], lp[3][G]; };
+template <int G, int D> constexpr bool early_side() { return G <= 4 && G * D <= 512; }
+
+template <int G>
+__device__ inline void request_side_rows(const AttnArgs& a, const SplitCtx& x, SideRows<G>& p)
+{
+    const int tid = threadIdx.x;
+    const float* logit_prev_u = a.logit_prev + x.ubase * G;
+    const float* score_u = a.score + x.ubase;
+#pragma unroll
+    for (int run = 0; run < 3; ++run) {
+        int lo, hi, phys0;
+        run_bounds(a, x, run, lo, hi, phys0);
+        const int lead = phys0 & 3, pa = phys0 - lead, cnt = hi - lo + lead;
+        if (a.pending && hi - lo > 0 && 4 * tid < cnt) {
+            p.sc[run] = *(const float4*)(score_u + pa + 4 * tid);
+#pragma unroll
+            for (int g = 0; g < G; ++g) p.lp[run][g] = *(const float4*)(logit_prev_u + (size_t)g * a.cap + pa + 4 * tid);
+        }
+    }
+}
+
+// new score = old score + sum over heads of the previous step's probability (lazy update, one step late)
+template <int G>
+__device__ inline void first_pass_scores(const AttnArgs& a, const SplitCtx& x, const PrevStat<G>& prev, SideRows<G>& p)
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int run = 0; run < 3; ++run) {
+        int lo, hi, phys0;
+        run_bounds(a, x, run, lo, hi, phys0);
+        const int lead = phys0 & 3, cnt = hi - lo + lead;
+        if (a.pending && hi - lo > 0 && 4 * tid < cnt) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                p.sc[run].x += fast_exp2(p.lp[run][g].x - prev.M[g]) * prev.iL[g];
+                p.sc[run].y += fast_exp2(p.lp[run][g].y - prev.M[g]) * prev.iL[g];
+                p.sc[run].z += fast_exp2(p.lp[run][g].z - prev.M[g]) * prev.iL[g];
+                p.sc[run].w += fast_exp2(p.lp[run][g].w - prev.M[g]) * prev.iL[g];
+            }
+        }
+    }
+}
+
 template <int G, int D, int NW>
-__device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const float* stage,
-                                    float (*sm_m)[G], float (*sm_l)[G], float (*sm_acc)[G][D], float* sm_ml,
-                                    int* sm_ticket)
+__device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const PrevStat<G>& prev,
+                                    const float4 (&pre_sc)[3], const float* stage,
+                                    float (*sm_m)[G], float (*sm_l)[G], float (*sm_acc)[G][D], int* sm_ticket)
 {
     constexpr int NTHR = NW * 64;                         // threads per block
     const int tid = threadIdx.x;
@@ -183,26 +311,8 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
     float* logit_u = a.logit + x.ubase * G;               // [G][cap] for this unit, written by this step
     const float* logit_prev_u = a.logit_prev + x.ubase * G;   // the previous step's logits
     float* score_u = a.score + x.ubase;
-    float Mp[G], iLp[G];                                   // previous step's global max and 1/sum per head
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        Mp[g] = a.pending ? a.stat_prev[((size_t)unit * G + g) * 2] : 0.f;
-        iLp[g] = a.pending ? a.stat_prev[((size_t)unit * G + g) * 2 + 1] : 0.f;
-    }
-
-    // 1. side-phase inputs of the first pass (4 rows per thread) of each stored run
-    float4 pre_sc[3], pre_lp[3][G];
-#pragma unroll
-    for (int run = 0; run < 3; ++run) {
-        int lo, hi, phys0;
-        run_bounds(a, x, run, lo, hi, phys0);
-        const int lead = phys0 & 3, pa = phys0 - lead, cnt = hi - lo + lead;
-        if (a.pending && hi - lo > 0 && 4 * tid < cnt) {
-            pre_sc[run] = *(const float4*)(score_u + pa + 4 * tid);
-#pragma unroll
-            for (int g = 0; g < G; ++g) pre_lp[run][g] = *(const float4*)(logit_prev_u + (size_t)g * a.cap + pa + 4 * tid);
-        }
-    }
+    const float (&Mp)[G] = prev.M;
+    const float (&iLp)[G] = prev.iL;
 
     // 2. merge the waves; the only split writes the result, otherwise publish the partial
     __syncthreads();
@@ -236,8 +346,54 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
         }
     }
 
-    // 3. dense side phase, after the read stream of this block is over (the logits staged by all waves are
-    // visible after the barrier above).  Four consecutive physical rows per thread, 16-byte accesses where
+    if (tid == 0) BUZZ_STAMP(2);
+
+    // 3. ticket: the block that arrives last for this unit sees every split's partial.  Every wave first
+    // waits until its own published (write-through) stores have been acknowledged (vmcnt(0)), then the
+    // block synchronises, then one thread takes the ticket: the ticket can never overtake a partial.
+    // No cache maintenance is involved.
+    bool last = false;
+    if (S > 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0), expcnt / lgkmcnt untouched
+        __syncthreads();
+        if (tid == 0) *sm_ticket = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        last = *sm_ticket == S - 1;
+        if (tid == 0) BUZZ_STAMP(4);
+    }
+
+    // 4. in the last block the upper half of the waves merges the splits; each of those threads owns OPT
+    // output elements and requests, for the first CH splits, the element itself and the (max, sum) pair of
+    // its head -- everything in ONE round of device-scope loads with no branch in between.  The answers
+    // arrive while the block does its side phase, which for up to 4 * NTHR / 2 rows per split keeps only
+    // the lower half of the waves busy.
+    constexpr int NM = NTHR / 2;                          // merging threads
+    constexpr int OPT = (G * D + NM - 1) / NM;            // output elements per merging thread
+    constexpr int CH = OPT >= 16 ? 2 : (OPT >= 8 ? 4 : 8);   // splits per round of loads
+    const bool merger = last && tid >= NM;
+    const unsigned long long* ml = (const unsigned long long*)(a.part_ml + (size_t)unit * a.s_cap * G * 2);
+    const float* po = a.part_o + (size_t)unit * a.s_cap * G * D;
+    unsigned long long mlr[OPT][CH];
+    float xr[OPT][CH];
+    auto request = [&](int s0) {
+#pragma unroll
+        for (int r = 0; r < OPT; ++r) {
+            const int i = min(tid - NM + NM * r, G * D - 1);
+            const int g = i / D;
+#pragma unroll
+            for (int e = 0; e < CH; ++e) {
+                const int sp = min(s0 + e, S - 1);
+                mlr[r][e] = __hip_atomic_load(ml + sp * G + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                xr[r][e] = acquire(po + (size_t)sp * G * D + i);
+            }
+        }
+    };
+    if (last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (merger) request(0);
+
+    // 5. dense side phase, after the read stream of this block is over (the logits staged by all waves are
+    // visible after the barriers above).  Four consecutive physical rows per thread, 16-byte accesses where
     // the whole group belongs to this split; the appended row starts from score 0.
     // (Doing the score update at the start of the block instead, under the latency of the first K/V
     // loads, was measured 8% slower: its writes then compete with the ramping read stream.)
@@ -253,22 +409,20 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
             const int ph = pa + r0;
             float4 sc = make_float4(0.f, 0.f, 0.f, 0.f);
             if (upd) {
-                float4 lp[G];
-                if (run < 3 && r0 == 4 * tid) {           // first pass: requested in step 1
+                if (run < 3 && r0 == 4 * tid) {           // first pass: worked out in step 2b
                     sc = pre_sc[run < 3 ? run : 0];
-#pragma unroll
-                    for (int g = 0; g < G; ++g) lp[g] = pre_lp[run < 3 ? run : 0][g];
                 } else {
+                    float4 lp[G];
                     sc = *(const float4*)(score_u + ph);
 #pragma unroll
                     for (int g = 0; g < G; ++g) lp[g] = *(const float4*)(logit_prev_u + (size_t)g * a.cap + ph);
-                }
 #pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    sc.x += fast_exp2(lp[g].x - Mp[g]) * iLp[g];
-                    sc.y += fast_exp2(lp[g].y - Mp[g]) * iLp[g];
-                    sc.z += fast_exp2(lp[g].z - Mp[g]) * iLp[g];
-                    sc.w += fast_exp2(lp[g].w - Mp[g]) * iLp[g];
+                    for (int g = 0; g < G; ++g) {
+                        sc.x += fast_exp2(lp[g].x - Mp[g]) * iLp[g];
+                        sc.y += fast_exp2(lp[g].y - Mp[g]) * iLp[g];
+                        sc.z += fast_exp2(lp[g].z - Mp[g]) * iLp[g];
+                        sc.w += fast_exp2(lp[g].w - Mp[g]) * iLp[g];
+                    }
                 }
             }
             const int sj = lo - j0 + r0 - lead;           // staging index of the group's first row
@@ -292,72 +446,46 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
             }
         }
     }
-    if (S == 1) return;
+    if (tid == 0) BUZZ_STAMP(3);
+    if (!merger) return;
 
-    // 4. ticket: the block that arrives last for this unit sees every split's partial.  Every wave first
-    // waits until its own published (write-through) stores have been acknowledged (vmcnt(0)), then the
-    // block synchronises, then one thread takes the ticket: the ticket can never overtake a partial.
-    // No cache maintenance is involved.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0), expcnt / lgkmcnt untouched
-    __syncthreads();
-    if (tid == 0) *sm_ticket = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (*sm_ticket != S - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    if (tid == 0) __hip_atomic_store(a.ticket + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next step
-
-    // 5. merge the splits: every load of the first 16 splits is issued before anything waits
-    constexpr int OPT = (G * D + NTHR - 1) / NTHR;              // output elements per thread
-    constexpr int CH = 16;                                // splits per round of loads
-    const float* ml = a.part_ml + (size_t)unit * a.s_cap * G * 2;
-    const float* po = a.part_o + (size_t)unit * a.s_cap * G * D;
-    float mlv[(2 * kMaxSplits * G + NTHR - 1) / NTHR];
+    // 6. merge the splits: a running (max, sum, output) per owned element, CH splits per round
+    float Mr[OPT], Lr[OPT], Or[OPT];
 #pragma unroll
-    for (int k = 0; k < (int)(sizeof(mlv) / sizeof(float)); ++k) {
-        const int i = tid + NTHR * k;                     // element i of [S][G][2]
-        mlv[k] = i < S * G * 2 ? acquire(ml + i) : 0.f;
-    }
-    float x0[OPT][CH];
+    for (int r = 0; r < OPT; ++r) { Mr[r] = -INFINITY; Lr[r] = 0.f; Or[r] = 0.f; }
+    for (int s0 = 0; s0 < S; s0 += CH) {
+        if (s0 > 0) request(s0);
 #pragma unroll
-    for (int r = 0; r < OPT; ++r) {
-        const int i = tid + NTHR * r;
+        for (int r = 0; r < OPT; ++r) {
+            float mx = Mr[r];
 #pragma unroll
-        for (int e = 0; e < CH; ++e) x0[r][e] = (i < G * D && e < S) ? acquire(po + (size_t)e * G * D + i) : 0.f;
-    }
+            for (int e = 0; e < CH; ++e)
+                if (s0 + e < S) mx = fmaxf(mx, __uint_as_float((unsigned)mlr[r][e]));   // finite: the appended row is always present
+            const float keep = fast_exp2(Mr[r] - mx);    // 0 in the first round
+            Lr[r] *= keep; Or[r] *= keep; Mr[r] = mx;
 #pragma unroll
-    for (int k = 0; k < (int)(sizeof(mlv) / sizeof(float)); ++k) {
-        const int i = tid + NTHR * k;
-        if (i < S * G * 2) sm_ml[(i & 1) * kMaxSplits * G + (i >> 1)] = mlv[k];   // [0]: max, [1]: sum, each [S][G]
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < OPT; ++r) {
-        const int i = tid + NTHR * r;
-        if (i >= G * D) continue;
-        const int g = i / D;
-        float M = -INFINITY;
-        for (int sp = 0; sp < S; ++sp) M = fmaxf(M, sm_ml[sp * G + g]);   // finite: the appended row is always present
-        float L = 0.f, o = 0.f;
-#pragma unroll
-        for (int e = 0; e < CH; ++e) {
-            if (e < S) {
-                const float w = fast_exp2(sm_ml[e * G + g] - M);
-                L = fmaf(sm_ml[kMaxSplits * G + e * G + g], w, L);
-                o = fmaf(w, x0[r][e], o);
+            for (int e = 0; e < CH; ++e) {
+                if (s0 + e < S) {
+                    const float w = fast_exp2(__uint_as_float((unsigned)mlr[r][e]) - mx);
+                    Lr[r] = fmaf(__uint_as_float((unsigned)(mlr[r][e] >> 32)), w, Lr[r]);
+                    Or[r] = fmaf(w, xr[r][e], Or[r]);
+                }
             }
         }
-        for (int sp = CH; sp < S; ++sp) {                 // beyond the first round: one more load each
-            const float w = fast_exp2(sm_ml[sp * G + g] - M);
-            L = fmaf(sm_ml[kMaxSplits * G + sp * G + g], w, L);
-            o = fmaf(w, acquire(po + (size_t)sp * G * D + i), o);
-        }
-        outp[i] = o / L;
+    }
+#pragma unroll
+    for (int r = 0; r < OPT; ++r) {
+        const int i = tid - NM + NM * r;
+        if (i >= G * D) continue;
+        const int g = i / D;
+        outp[i] = Or[r] / Lr[r];
         if (i - g * D == 0) {
-            a.stat[((size_t)unit * G + g) * 2] = M;
-            a.stat[((size_t)unit * G + g) * 2 + 1] = 1.0f / L;
+            a.stat[((size_t)unit * G + g) * 2] = Mr[r];
+            a.stat[((size_t)unit * G + g) * 2 + 1] = 1.0f / Lr[r];
         }
     }
+    if (tid == NM) __hip_atomic_store(a.ticket + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next step
+    if (tid == NM) BUZZ_STAMP(5);
 }
 
 // Vector-ALU streaming kernel (any dtype; the choice for one query head per kv head).
@@ -376,13 +504,16 @@ __global__ __launch_bounds__(NW * 64, BUZZ_MIN_BLOCKS) void attn_split_kernel(co
     extern __shared__ float stage[];                      // [G][rows_per_split] logits of this split's rows
     __shared__ float sm_m[NW][G], sm_l[NW][G];
     __shared__ float sm_acc[NW][G][D];
-    __shared__ float sm_ml[2 * kMaxSplits * G];
-    __shared__ int sm_ticket;
+    __shared__ int sm_ticket, sm_next;
 
     const SplitCtx x = make_ctx(a);
     const int unit = x.unit, b = x.b, kvh = x.kvh, j0 = x.j0, j1 = x.j1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane % LPR, rs = lane / LPR;
+    const PrevStat<G> prev = load_prev_stat<G>(a, unit);
+    SideRows<G> side;
+    if constexpr (early_side<G, D>()) request_side_rows<G>(a, x, side);
+    if (tid == 0) { BUZZ_STAMP(0); BUZZ_STAMP_VALUE(6, __builtin_amdgcn_s_getreg((31 << 11) | 4)); BUZZ_STAMP_VALUE(7, __builtin_amdgcn_s_getreg((31 << 11) | 20)); }
 
     u32x4 qr[G];                                          // this lane's 16 bytes of every query head, raw
     {
@@ -465,50 +596,65 @@ __global__ __launch_bounds__(NW * 64, BUZZ_MIN_BLOCKS) void attn_split_kernel(co
         }
     };
 
-    for (int run = 0; run < 4; ++run) {
-        int lo, hi, phys0;
-        run_bounds(a, x, run, lo, hi, phys0);
-        if (hi - lo <= 0) continue;
-        const char *kp, *vp;
-        const int lead = phys0 & (WROWS - 1);             // rows between the aligned anchor and the run's first row
-        const int cnt = hi - lo + lead;                   // run length measured from the anchor
-        if (run < 3) {
-            kp = Kb + (size_t)phys0 * ROWB;
-            vp = Vb + (size_t)phys0 * ROWB;
-        } else {                                          // eq. 2: the new row comes from the caller and joins the cache
-            kp = (const char*)a.k_new + (size_t)unit * ROWB;
-            vp = (const char*)a.v_new + (size_t)unit * ROWB;
-            if (wave == 0 && rs == 0) {
-                *(u32x4*)(Kb + (size_t)a.new_phys * ROWB + lane_off) = *(const u32x4*)(kp + lane_off);
-                *(u32x4*)(Vb + (size_t)a.new_phys * ROWB + lane_off) = *(const u32x4*)(vp + lane_off);
-                if (c == 0) a.pos[ubase + a.new_phys] = a.new_pos;
-            }
+    if (tid == 0) sm_next = NW;                           // tiles 0 .. NW-1 are the waves' first tiles
+    __syncthreads();
+
+    // eq. 2: the new row comes from the caller, joins the cache, and is attended to like any other row
+    if (x.j1 == a.n && wave == 0) {
+        const char* kp = (const char*)a.k_new + (size_t)unit * ROWB;
+        const char* vp = (const char*)a.v_new + (size_t)unit * ROWB;
+        if (rs == 0) {
+            *(u32x4*)(Kb + (size_t)a.new_phys * ROWB + lane_off) = *(const u32x4*)(kp + lane_off);
+            *(u32x4*)(Vb + (size_t)a.new_phys * ROWB + lane_off) = *(const u32x4*)(vp + lane_off);
+            if (c == 0) a.pos[ubase + a.new_phys] = a.new_pos;
         }
-        // the block's waves take the run's tiles round-robin (a block-contiguous stream; measured ~5% faster
-        // than giving every wave its own contiguous piece)
-        constexpr int STEP = NW * WROWS;
-        if constexpr (G == 1) {
+        u32x4 kr[U], vr[U];
+        load_tile(kr, vr, kp, vp, 0, 0, 1);
+        compute_tile(kr, vr, 0, 0, 1, a.n - 1 - j0);
+    }
+
+    const TileMap<WROWS> tiles(a, x);
+    const int total = tiles.total();
+    auto load_t = [&](u32x4 (&kr)[U], u32x4 (&vr)[U], int t) {
+        int lo, phys0, lead, cnt, base;
+        tiles.locate(t, lo, phys0, lead, cnt, base);
+        load_tile(kr, vr, Kb + (size_t)phys0 * ROWB, Vb + (size_t)phys0 * ROWB, base, lead, cnt);
+    };
+    auto compute_t = [&](const u32x4 (&kr)[U], const u32x4 (&vr)[U], int t) {
+        int lo, phys0, lead, cnt, base;
+        tiles.locate(t, lo, phys0, lead, cnt, base);
+        compute_tile(kr, vr, base, lead, cnt, lo - j0 + base - lead);
+    };
+    if constexpr (G == 1) {
         // two tile buffers: the next tile's loads are issued before the current tile is consumed
         u32x4 ka[U], va[U], kb[U], vb[U];
-        int base = wave * WROWS;
-        if (base < cnt) load_tile(ka, va, kp, vp, base, lead, cnt);
-        while (base < cnt) {
-            if (base + STEP < cnt) load_tile(kb, vb, kp, vp, base + STEP, lead, cnt);
-            compute_tile(ka, va, base, lead, cnt, lo - j0 + base - lead);
-            base += STEP;
-            if (base >= cnt) break;
-            if (base + STEP < cnt) load_tile(ka, va, kp, vp, base + STEP, lead, cnt);
-            compute_tile(kb, vb, base, lead, cnt, lo - j0 + base - lead);
-            base += STEP;
+        int t = wave, tn = next_tile(a, &sm_next, t, NW);
+        if (t < total) load_t(ka, va, t);
+        while (t < total) {
+            if (tn < total) load_t(kb, vb, tn);
+            int tnn = next_tile(a, &sm_next, tn, NW);
+            compute_t(ka, va, t);
+            t = tn; tn = tnn;
+            if (t >= total) break;
+            if (tn < total) load_t(ka, va, tn);
+            tnn = next_tile(a, &sm_next, tn, NW);
+            compute_t(kb, vb, t);
+            t = tn; tn = tnn;
         }
-        } else {
-        for (int base = wave * WROWS; base < cnt; base += STEP) {
+    } else {
+        int t = wave;
+        while (t < total) {
             u32x4 kr[U], vr[U];
-            load_tile(kr, vr, kp, vp, base, lead, cnt);
-            compute_tile(kr, vr, base, lead, cnt, lo - j0 + base - lead);
-        }
+            load_t(kr, vr, t);
+            const int tn = next_tile(a, &sm_next, t, NW);
+            compute_t(kr, vr, t);
+            t = tn;
         }
     }
+
+    if (lane == 0) BUZZ_STAMP(8 + (wave & 7));
+    if constexpr (!early_side<G, D>()) request_side_rows<G>(a, x, side);
+    first_pass_scores<G>(a, x, prev, side);
 
     // merge the RPW lane groups of this wave (same columns, different rows)
 #pragma unroll
@@ -543,7 +689,7 @@ __global__ __launch_bounds__(NW * 64, BUZZ_MIN_BLOCKS) void attn_split_kernel(co
         }
     }
     (void)j1;
-    finish_split<G, D, NW>(a, x, stage, sm_m, sm_l, sm_acc, sm_ml, &sm_ticket);
+    finish_split<G, D, NW>(a, x, prev, side.sc, stage, sm_m, sm_l, sm_acc, &sm_ticket);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -603,18 +749,22 @@ __global__ __launch_bounds__(NW * 64) void attn_split_mfma_kernel(const AttnArgs
     constexpr int QP = NCH / 4;                           // K / Q chunks per lane
     constexpr int VS = (NCH + 15) / 16;                   // sets of 16 column chunks
     constexpr int WROWS = 16;
+    constexpr int TR = BUZZ_MFMA_TR;                      // tiles a wave loads before it computes
     static_assert(G >= 2 && G <= 16 && NCH % 4 == 0, "grouped queries, head_dim multiple of 32");
 
     extern __shared__ float stage[];                      // [G][rows_per_split] logits of this split's rows
     __shared__ float sm_m[NW][G], sm_l[NW][G];
     __shared__ float sm_acc[NW][G][D];
-    __shared__ float sm_ml[2 * kMaxSplits * G];
-    __shared__ int sm_ticket;
+    __shared__ int sm_ticket, sm_next;
 
     const SplitCtx x = make_ctx(a);
     const int unit = x.unit, j0 = x.j0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, q = lane >> 4;
+    const PrevStat<G> prev = load_prev_stat<G>(a, unit);
+    SideRows<G> side;
+    if constexpr (early_side<G, D>()) request_side_rows<G>(a, x, side);
+    if (tid == 0) { BUZZ_STAMP(0); BUZZ_STAMP_VALUE(6, __builtin_amdgcn_s_getreg((31 << 11) | 4)); BUZZ_STAMP_VALUE(7, __builtin_amdgcn_s_getreg((31 << 11) | 20)); }
 
     u32x4 qb[QP];                                         // Q operand: head j, chunks 4p + q
 #pragma unroll
@@ -706,32 +856,47 @@ __global__ __launch_bounds__(NW * 64) void attn_split_mfma_kernel(const AttnArgs
         }
     };
 
-    for (int run = 0; run < 4; ++run) {
-        int lo, hi, phys0;
-        run_bounds(a, x, run, lo, hi, phys0);
-        if (hi - lo <= 0) continue;
-        const char *kp, *vp;
-        const int lead = phys0 & (WROWS - 1);             // rows between the aligned anchor and the run's first row
-        const int cnt = hi - lo + lead;                   // run length measured from the anchor
-        if (run < 3) {
-            kp = Kb + (size_t)phys0 * ROWB;
-            vp = Vb + (size_t)phys0 * ROWB;
-        } else {                                          // eq. 2: the new row comes from the caller and joins the cache
-            kp = (const char*)a.k_new + (size_t)unit * ROWB;
-            vp = (const char*)a.v_new + (size_t)unit * ROWB;
-            if (tid < NCH) {
-                *(u32x4*)(Kb + (size_t)a.new_phys * ROWB + tid * 16) = *(const u32x4*)(kp + tid * 16);
-                *(u32x4*)(Vb + (size_t)a.new_phys * ROWB + tid * 16) = *(const u32x4*)(vp + tid * 16);
-                if (tid == 0) a.pos[x.ubase + a.new_phys] = a.new_pos;
-            }
+    if (tid == 0) sm_next = NW;                           // tiles 0 .. NW-1 are the waves' first tiles
+    __syncthreads();
+
+    // eq. 2: the new row comes from the caller, joins the cache, and is attended to like any other row
+    if (x.j1 == a.n && wave == 0) {
+        const char* kp = (const char*)a.k_new + (size_t)unit * ROWB;
+        const char* vp = (const char*)a.v_new + (size_t)unit * ROWB;
+        if (tid < NCH) {
+            *(u32x4*)(Kb + (size_t)a.new_phys * ROWB + tid * 16) = *(const u32x4*)(kp + tid * 16);
+            *(u32x4*)(Vb + (size_t)a.new_phys * ROWB + tid * 16) = *(const u32x4*)(vp + tid * 16);
+            if (tid == 0) a.pos[x.ubase + a.new_phys] = a.new_pos;
         }
-        for (int base = wave * WROWS; base < cnt; base += NW * WROWS) {   // waves take tiles round-robin
-            u32x4 kk[QP], vv[VS][4];                      // (double-buffering was measured 4% slower here)
-            load_tile(kk, vv, kp, vp, base, lead, cnt);
-            compute_tile(kk, vv, base, lead, cnt, lo - j0 + base - lead);
-        }
+        u32x4 kk[QP], vv[VS][4];
+        load_tile(kk, vv, kp, vp, 0, 0, 1);
+        compute_tile(kk, vv, 0, 0, 1, a.n - 1 - j0);
     }
 
+    // groups of TR tiles: all loads of a group are in flight before its first tile is used
+    const TileMap<WROWS * TR> tiles(a, x);
+    const int total = tiles.total();
+    int t = wave;
+    while (t < total) {
+        int lo, phys0, lead, cnt, base;
+        tiles.locate(t, lo, phys0, lead, cnt, base);
+        const char* kp = Kb + (size_t)phys0 * ROWB;
+        const char* vp = Vb + (size_t)phys0 * ROWB;
+        u32x4 kk[TR][QP], vv[TR][VS][4];
+#pragma unroll
+        for (int u = 0; u < TR; ++u)
+            if (u == 0 || base + u * WROWS < cnt) load_tile(kk[u], vv[u], kp, vp, base + u * WROWS, lead, cnt);
+        const int tn = next_tile(a, &sm_next, t, NW);
+#pragma unroll
+        for (int u = 0; u < TR; ++u)
+            if (u == 0 || base + u * WROWS < cnt)
+                compute_tile(kk[u], vv[u], base + u * WROWS, lead, cnt, lo - j0 + base + u * WROWS - lead);
+        t = tn;
+    }
+
+    if (lane == 0) BUZZ_STAMP(8 + (wave & 7));
+    if constexpr (!early_side<G, D>()) request_side_rows<G>(a, x, side);
+    first_pass_scores<G>(a, x, prev, side);
     // this wave's result into LDS in the layout finish_split expects
     float l_tot = l_run + __shfl_xor(l_run, 16);
     l_tot += __shfl_xor(l_tot, 32);
@@ -749,7 +914,7 @@ __global__ __launch_bounds__(NW * 64) void attn_split_mfma_kernel(const AttnArgs
             }
         }
     }
-    finish_split<G, D, NW>(a, x, stage, sm_m, sm_l, sm_acc, sm_ml, &sm_ticket);
+    finish_split<G, D, NW>(a, x, prev, side.sc, stage, sm_m, sm_l, sm_acc, &sm_ticket);
 }
 
 constexpr int kScoreRowsPerBlock = 2048;
@@ -794,17 +959,18 @@ hipError_t launch_split_t(const AttnArgs& a, int units, hipStream_t st, Timing t
             else BUZZ_LAUNCH((attn_split_mfma_kernel<T, D, G, false, 4>), grid, block, lds, st, tm, a);
         }
         return hipGetLastError();
-    }
-    constexpr int RPW = 64 / (D / Elem<T>::VEC);
-    constexpr int U = unroll_for<G>() * RPW >= 4 ? unroll_for<G>() : 4 / RPW;   // a trip covers at least 4 rows
-    if (a.waves == 8) {
-        if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, true, 8>), grid, block, lds, st, tm, a);
-        else BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, false, 8>), grid, block, lds, st, tm, a);
     } else {
-        if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, true, 4>), grid, block, lds, st, tm, a);
-        else BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, false, 4>), grid, block, lds, st, tm, a);
+        constexpr int RPW = 64 / (D / Elem<T>::VEC);
+        constexpr int U = unroll_for<G>() * RPW >= 4 ? unroll_for<G>() : 4 / RPW;   // a trip covers at least 4 rows
+        if (a.waves == 8) {
+            if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, true, 8>), grid, block, lds, st, tm, a);
+            else BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, false, 8>), grid, block, lds, st, tm, a);
+        } else {
+            if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, true, 4>), grid, block, lds, st, tm, a);
+            else BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, false, 4>), grid, block, lds, st, tm, a);
+        }
+        return hipGetLastError();
     }
-    return hipGetLastError();
 }
 
 template <typename T, int D>
@@ -842,6 +1008,14 @@ hipError_t launch_attn_split_fp32(int D, int G, const AttnArgs& a, int units, hi
 #elif BUZZ_TU == 1
 hipError_t launch_attn_split_fp16(int D, int G, const AttnArgs& a, int units, hipStream_t st, Timing tm) { return launch_split_d<fp16_t>(D, G, a, units, st, tm); }
 #elif BUZZ_TU == 2
+#ifdef BUZZ_TRACE
+}  // namespace buzz
+extern "C" int buzz_debug_trace_read(void* host, size_t bytes)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(buzz::g_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+namespace buzz {
+#endif
 hipError_t launch_attn_split_bf16(int D, int G, const AttnArgs& a, int units, hipStream_t st, Timing tm) { return launch_split_d<bf16_t>(D, G, a, units, st, tm); }
 #else
 hipError_t launch_attn_split_fp32(int D, int G, const AttnArgs& a, int units, hipStream_t st, Timing tm);
@@ -859,7 +1033,7 @@ int attn_tile_rows(int dtype, int D, int G)
 {
     const int vec = dtype == BUZZ_FP32 ? 4 : 8;
     const int rpw = 64 / (D / vec);
-    if (G >= 2 && dtype != BUZZ_FP32) return 4 * 16;      // matrix-core kernel: 16-row tiles
+    if (G >= 2 && dtype != BUZZ_FP32) return 16;          // matrix-core kernel: 16-row tiles
     int u = G == 1 ? BUZZ_U_G1 : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
     if (u * rpw < 4) u = 4 / rpw;
     return 4 * rpw * u;

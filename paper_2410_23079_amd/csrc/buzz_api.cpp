@@ -31,7 +31,7 @@ int make_layout(const buzz_config_t* c, Layout* L)
     if (c->sink < 0 || c->window < 0 || c->segment < 1 || c->keep < 0 || c->evict_every < 1) return BUZZ_EINVAL;
     if (c->old_stride < 0 || c->max_context < 1 || c->capacity < 0 || c->reserved != 0) return BUZZ_EINVAL;
     if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN | BUZZ_FLAG_STREAMING | BUZZ_FLAG_CACHED |
-                              BUZZ_FLAG_LOG_N | BUZZ_FLAG_THRESHOLD_TOTAL))
+                              BUZZ_FLAG_LOG_N | BUZZ_FLAG_THRESHOLD_TOTAL | BUZZ_FLAG_DETERMINISTIC))
         return BUZZ_EINVAL;
     if ((c->flags & BUZZ_FLAG_STREAMING) && (c->flags & BUZZ_FLAG_CACHED)) return BUZZ_EINVAL;
     if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BUZZ_EINVAL;
@@ -487,6 +487,7 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         const double step_bytes = (double)L.units * (double)n * 2.0 * L.row_bytes;
         a.streaming = (cfg.flags & BUZZ_FLAG_STREAMING) ? 1
                       : (cfg.flags & BUZZ_FLAG_CACHED) ? 0 : (step_bytes > kLastLevelCacheBytes);
+        a.fixed_tiles = (cfg.flags & BUZZ_FLAG_DETERMINISTIC) ? 1 : 0;
         const int tile = attn_tile_rows(cfg.kv_dtype, cfg.head_dim, L.G);
         // Few, long blocks amortise the per-block merge, and a block count that fills every compute unit the
         // same number of times avoids a tail.  Automatic choice: one block per compute unit, 8 waves wide
@@ -497,13 +498,15 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         if (S < 1) S = 1;
         if (S > L.s_cap) S = L.s_cap;
         int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
-        while ((rps + 4) * L.G > kStageFloats) {               // LDS staging bound (+ alignment slack); s_cap covers it
+        const int stage_cap = stage_floats(L.G, cfg.head_dim);
+        while ((rps + 4) * L.G > stage_cap) {                  // LDS staging bound (+ alignment slack); s_cap covers it
             S += 1;
             rps = ceil_div(ceil_div(n, S), tile) * tile;
         }
         a.rows_per_split = (int32_t)rps;
         a.n_splits = (int32_t)ceil_div(n, rps);
-        a.waves = (int64_t)L.units * a.n_splits <= cus ? 8 : 4;   // keep about 8 waves per compute unit
+        // about 8 waves per compute unit; 4-wave blocks also where 8 waves' partial outputs would not fit the LDS
+        a.waves = ((int64_t)L.units * a.n_splits <= cus && L.G * cfg.head_dim < kWideBlockMaxGD) ? 8 : 4;
         if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st, prof_pair(c, 0)))
             return hip_rc(e);
         if (c->prof) c->prof_row_bytes += (double)L.units * (double)n * 2.0 * L.row_bytes;

@@ -25,7 +25,24 @@ constexpr int kMaxSplits = 128;        // upper bound on key-range splits per un
 constexpr int kDefaultCUs = 256;       // MI355X; replaced by the device's own count at the first launch
 constexpr int kMaxBlocks = 4096;       // partial buffers are sized for units * splits <= this (or 1 split per unit)
 constexpr int kMaxSegment = 4096;
-constexpr int kStageFloats = 4096;     // LDS logit staging of one split: rows_per_split * group size <= this
+constexpr int kStageFloats = 4096;     // LDS logit staging of one split that every shape can have
+constexpr int kStageFloatsMax = 8192;  // ... and what a shape gets when the block's other LDS arrays leave room
+
+constexpr int kWideBlockMaxGD = 2048;  // 8-wave decode blocks only below this group size * head_dim (LDS)
+
+// Floats of LDS staging (rows_per_split * group size) a decode block may use: as much as keeps the block's
+// LDS (the waves' partial outputs [waves][G][D] and running statistics, the staging) within 64 KB, between
+// kStageFloats and kStageFloatsMax.  A larger staging area lets one split cover a longer row range, so a
+// unit needs fewer splits; the workspace bound on the split count assumes kStageFloats.
+inline int stage_floats(int G, int D)
+{
+    const int waves = G * D < kWideBlockMaxGD ? 8 : 4;
+    const int fixed = waves * G * D * 4 + 2 * 8 * G * 4 + 64;
+    int f = (65536 - fixed) / 4;
+    if (f > kStageFloatsMax) f = kStageFloatsMax;
+    if (f < kStageFloats) f = kStageFloats;
+    return f;
+}
 constexpr double kLastLevelCacheBytes = 256.0 * 1024 * 1024;   // Infinity Cache of one MI355X      // segment scores of one wave must fit its LDS slice
 
 struct RingMap {
@@ -69,6 +86,7 @@ struct AttnArgs {
     int32_t waves;       // waves per block: 4, or 8 when every unit is a single split
     int32_t pending;     // 1: the previous step's score update has not been applied yet
     int32_t streaming;   // 1: K/V are read with the non-temporal hint (working set exceeds the last-level cache)
+    int32_t fixed_tiles; // 1: waves take tiles in a fixed round-robin (bitwise reproducible results)
     float scale_log2;    // softmax scale * log2(e)
 };
 

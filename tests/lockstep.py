@@ -15,12 +15,14 @@ import numpy as np
 import torch
 
 from oracle.buzz_oracle import OracleCache, OracleConfig
-from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_LOG_N, FLAG_THRESHOLD_TOTAL, BuzzCache, BuzzConfig
+from paper_2410_23079_amd import (FLAG_AUTO_EVICT, FLAG_DETERMINISTIC, FLAG_LOG_N, FLAG_THRESHOLD_TOTAL, BuzzCache,
+                                 BuzzConfig)
 from workloads import Workload
 
 OUT_TOL = 2e-3      # contract: max |o - o_ref| / max |o_ref| per (batch, head) vector
 OUT_EXPECT = 1e-4   # what fp32 accumulation over exactly widened inputs should reach (regression guard)
 SCORE_TOL = 1e-4    # relative to max(1, |score|)
+REPRO_TOL = 1e-5    # two runs without FLAG_DETERMINISTIC: same rows summed in another order
 
 
 def buzz_config(wl: Workload, flags=0, max_context=None, **over) -> BuzzConfig:
@@ -74,7 +76,7 @@ def gpu_prompt_scores(wl: Workload, prompt, n_obs: int, flags: int = 0):
 
 
 def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=None, splits=0,
-                 check_auto=True, capacity=0, log_n=False, threshold_total=False):
+                 check_auto=True, capacity=0, log_n=False, threshold_total=False, deterministic=True):
     """Returns a dict of the worst errors seen; raises AssertionError on any parity failure."""
     G, D = wl.group, wl.head_dim
     N = prompt["K"].shape[2]
@@ -86,7 +88,8 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
     uidx_b = torch.tensor([b for b, _ in units])
     uidx_h = torch.tensor([h for _, h in units])
     stats = dict(out=0.0, score=0.0, prefill_score=0.0, evictions=0)
-    vflags = (FLAG_LOG_N if log_n else 0) | (FLAG_THRESHOLD_TOTAL if threshold_total else 0)
+    vflags = ((FLAG_LOG_N if log_n else 0) | (FLAG_THRESHOLD_TOTAL if threshold_total else 0)
+              | (FLAG_DETERMINISTIC if deterministic else 0))
     okw = dict(log_n=log_n, threshold_total=threshold_total)
 
     # ---- prompt scores: library vs oracle, then shared
@@ -145,7 +148,11 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
         assert e <= OUT_EXPECT, f"step {t}: output error {e} above what fp32 accumulation should give"
         if auto is not None:
             auto.decode_step(q, k, v, out_auto)
-            assert torch.equal(out, out_auto), f"step {t}: auto-evict cache diverged from the manual one"
+            if deterministic:
+                assert torch.equal(out, out_auto), f"step {t}: auto-evict cache diverged from the manual one"
+            else:                                          # same rows, summed in a timing-dependent order
+                e2 = rel_err(unit_slices(out_auto, units, G), got.astype(np.float64))
+                assert e2 <= REPRO_TOL, f"step {t}: two runs of the default mode differ by {e2}"
         _, n_old_now, new_now = gpu.lengths()
         if (n_old_now + new_now if threshold_total else new_now) >= T:
             sg = compare_state(f"step {t} before eviction")
@@ -158,8 +165,11 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
     if auto is not None:
         a, b = gpu.export(), auto.export()
         assert gpu.lengths() == auto.lengths()
-        for x, y in zip(a, b):
-            assert torch.equal(x, y), "auto-evict cache differs from the manually evicted one"
+        for i, (x, y) in enumerate(zip(a, b)):               # K, V, score, pos
+            if i == 2 and not deterministic:
+                assert torch.allclose(x, y, rtol=REPRO_TOL, atol=REPRO_TOL), "scores of two default-mode runs differ"
+            else:
+                assert torch.equal(x, y), "auto-evict cache differs from the manually evicted one"
         auto.close()
     gpu.close()
     return stats
