@@ -69,7 +69,11 @@ enum {
        cache rows from a shared counter, so which wave sums which rows depends on timing and the outputs and
        scores of two identical runs may differ in the last bits (always within the stated tolerances).  With
        this flag the assignment is fixed; measured cost: up to 5% of the step. */
-    BUZZ_FLAG_DETERMINISTIC = 64u
+    BUZZ_FLAG_DETERMINISTIC = 64u,
+    /* Ablation "no local max" (Sec. 4.4): new tokens are interval-sampled like old ones -- the first `keep`
+       rows of every segment survive whatever their scores.  (The other ablation of that section, swapped
+       strides, needs no flag: segment = s^ and old_stride = s.) */
+    BUZZ_FLAG_INTERVAL_NEW = 128u
 };
 
 /* Symbols follow the paper's notation table (Sec. 3.3). */

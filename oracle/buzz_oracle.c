@@ -42,7 +42,8 @@
  *     softmax scale by log(n)/log(512), n = number of tokens the query sees,
  *     itself included; and the threshold may instead bound old + new tokens
  *     together, which is how the proof of the Parameter Estimation theorem
- *     reads T.
+ *     reads T; the ablation of Sec. 4.4 that drops the local-max function
+ *     keeps the first rows of every segment instead of the highest-scoring.
  */
 #include <math.h>
 #include <stdint.h>
@@ -59,7 +60,9 @@ typedef struct {
     int32_t old_stride;  /* s^ ; 0 => floor((s+1)/2) */
     int32_t auto_evict;  /* decode_step evicts by itself when the count reaches T */
     int32_t variant;     /* bit 0: log-n scaled attention (Sec. 3.5): scale *= log(n)/log(512), n = tokens so far
-                            bit 1: T bounds old + new tokens together (the reading used by the theorem's proof) */
+                            bit 1: T bounds old + new tokens together (the reading used by the theorem's proof)
+                            bit 2: ablation "no local max" (Sec. 4.4): new tokens are interval-sampled too, i.e.
+                                   the first `keep` rows of every segment survive whatever their scores */
     int64_t capacity;    /* logical row bound used by Remark 2; 0 => none */
     double  softmax_scale; /* 0 => 1/sqrt(head_dim) */
 } oracle_config;
@@ -176,8 +179,11 @@ static int unit_evict(const oracle_config *c, unit_t *x)
         /* a row survives iff fewer than `take` rows of its segment rank before it */
         for (int64_t j = idx; j < end; ++j) {
             int64_t before = 0;
-            for (int64_t i = idx; i < end; ++i)
-                if (i != j && ranks_before(x->A[i], i, x->A[j], j)) ++before;
+            for (int64_t i = idx; i < end; ++i) {
+                if (i == j) continue;
+                if (c->variant & 4) before += i < j;                       /* ablation: interval sampling, scores unused */
+                else if (ranks_before(x->A[i], i, x->A[j], j)) ++before;
+            }
             if (before < take) { keep_idx[m++] = j; ++cnt_new; }
         }
     }

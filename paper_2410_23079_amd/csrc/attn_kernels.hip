@@ -174,7 +174,7 @@ __device__ inline void run_bounds(const AttnArgs& a, const SplitCtx& x, int run,
     if (run == 0) { lo = x.j0; hi = min(x.jl1, a.map.front); phys0 = lo; }
     else if (run == 1) { lo = max(x.j0, a.map.front); hi = min(x.jl1, x.wrap); phys0 = a.map.ring_base + a.map.ring_head + (lo - a.map.front); }
     else if (run == 2) { lo = max(x.j0, x.wrap); hi = x.jl1; phys0 = a.map.ring_base + (lo - x.wrap); }
-    else { lo = a.n - 1; hi = x.j1 == a.n ? a.n : lo; phys0 = a.new_phys; }
+    else { lo = a.n - 1; hi = (x.j1 == a.n && x.j0 < a.n) ? a.n : lo; phys0 = a.new_phys; }
 }
 
 // Everything a block does once its waves have put their (max, sum, unnormalised output) into LDS.
@@ -600,7 +600,7 @@ __global__ __launch_bounds__(NW * 64, BUZZ_MIN_BLOCKS) void attn_split_kernel(co
     __syncthreads();
 
     // eq. 2: the new row comes from the caller, joins the cache, and is attended to like any other row
-    if (x.j1 == a.n && wave == 0) {
+    if (x.j1 == a.n && x.j0 < a.n && wave == 0) {
         const char* kp = (const char*)a.k_new + (size_t)unit * ROWB;
         const char* vp = (const char*)a.v_new + (size_t)unit * ROWB;
         if (rs == 0) {
@@ -860,7 +860,7 @@ __global__ __launch_bounds__(NW * 64) void attn_split_mfma_kernel(const AttnArgs
     __syncthreads();
 
     // eq. 2: the new row comes from the caller, joins the cache, and is attended to like any other row
-    if (x.j1 == a.n && wave == 0) {
+    if (x.j1 == a.n && x.j0 < a.n && wave == 0) {
         const char* kp = (const char*)a.k_new + (size_t)unit * ROWB;
         const char* vp = (const char*)a.v_new + (size_t)unit * ROWB;
         if (tid < NCH) {

@@ -31,7 +31,8 @@ int make_layout(const buzz_config_t* c, Layout* L)
     if (c->sink < 0 || c->window < 0 || c->segment < 1 || c->keep < 0 || c->evict_every < 1) return BUZZ_EINVAL;
     if (c->old_stride < 0 || c->max_context < 1 || c->capacity < 0 || c->reserved != 0) return BUZZ_EINVAL;
     if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN | BUZZ_FLAG_STREAMING | BUZZ_FLAG_CACHED |
-                              BUZZ_FLAG_LOG_N | BUZZ_FLAG_THRESHOLD_TOTAL | BUZZ_FLAG_DETERMINISTIC))
+                              BUZZ_FLAG_LOG_N | BUZZ_FLAG_THRESHOLD_TOTAL | BUZZ_FLAG_DETERMINISTIC |
+                              BUZZ_FLAG_INTERVAL_NEW))
         return BUZZ_EINVAL;
     if ((c->flags & BUZZ_FLAG_STREAMING) && (c->flags & BUZZ_FLAG_CACHED)) return BUZZ_EINVAL;
     if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BUZZ_EINVAL;
@@ -266,6 +267,7 @@ int evict_impl(buzz_cache_t* c, hipStream_t st)
             sa.score = c->at<float>(L.score); sa.unit_stride = L.cap;
             sa.map = c->map(); sa.lo = sa.map.front; sa.new_count = (int32_t)newc;
             sa.segment = cfg.segment; sa.keep = L.keep;
+            sa.ignore_scores = (cfg.flags & BUZZ_FLAG_INTERVAL_NEW) ? 1 : 0;
             sa.sel = c->at<int32_t>(L.sel); sa.sel_stride = L.sel_stride;
             if (hipError_t e = launch_segment_topk(sa, L.units, st, prof_pair(c, 2))) return hip_rc(e);
             GatherArgs g = cache_gather_base(c);
@@ -418,6 +420,7 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
                 sa.map = RingMap{0, 0, 0, 0};
                 sa.lo = (int32_t)k; sa.new_count = (int32_t)M;
                 sa.segment = cfg.segment; sa.keep = L.keep;
+                sa.ignore_scores = (cfg.flags & BUZZ_FLAG_INTERVAL_NEW) ? 1 : 0;
                 sa.sel = c->at<int32_t>(L.sel); sa.sel_stride = L.sel_stride;
                 if (hipError_t e = launch_segment_topk(sa, L.units, st)) return hip_rc(e);
                 GatherArgs gv = g;

@@ -97,6 +97,7 @@ struct SelectArgs {
     int32_t lo;                // logical index of the first new row
     int32_t new_count;         // rows to segment
     int32_t segment, keep;
+    int32_t ignore_scores;     // ablation: keep the first `keep` rows of every segment (interval sampling)
     int32_t* sel;              // [units][sel_stride] logical source rows of the survivors, increasing
     int32_t sel_stride;
 };

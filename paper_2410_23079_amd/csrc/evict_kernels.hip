@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void segment_topk_kernel(const SelectArgs a)
     const float* base = a.score + (size_t)unit * a.unit_stride;
     for (int e = lane; e < len; e += 64) {
         const int row = a.lo + start + e;
-        float v = base[a.map.ring_cap ? a.map.phys(row) : row];
+        float v = a.ignore_scores ? 0.f : base[a.map.ring_cap ? a.map.phys(row) : row];   // all equal: lowest indices win
         if (v != v) v = -INFINITY;                 // NaN ranks below everything
         sc[e] = v;
     }

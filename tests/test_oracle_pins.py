@@ -476,3 +476,23 @@ def test_total_threshold_runs_the_proofs_recurrence_by_itself(s):
     assert len(seen) >= 8
     predicted = (s * s + 1) / (s + 1) if s % 2 else (s - 1)
     assert abs(T / seen[-1] - predicted) / predicted < 0.03
+
+
+def test_interval_sampling_of_new_tokens_ignores_scores():
+    """Ablation without the local-max function (Sec. 4.4): survivors are fixed positions, whatever the scores."""
+    k, w, s, c, T, D = 2, 5, 4, 1, 11, 2
+    r = np.random.default_rng(31)
+    N = k + w + 2 * T + 3
+    K = r.standard_normal((1, 1, N, D)); V = r.standard_normal((1, 1, N, D))
+    o = OracleCache(OracleConfig(1, 1, 1, D, sink=k, window=w, segment=s, keep=c, evict_every=T, old_stride=1,
+                                 interval_new=True))
+    o.prefill(K, V, init_score=r.standard_normal((1, 1, N)))
+    pos = o.export()[3][0, 0]
+    mid = np.arange(k, N - w)
+    expect = np.concatenate([np.arange(k), mid[::s], np.arange(N - w, N)])          # plain strided slices
+    np.testing.assert_array_equal(pos, expect)
+    o2 = OracleCache(OracleConfig(1, 1, 1, D, sink=k, window=w, segment=s, keep=2, evict_every=T, old_stride=1,
+                                  interval_new=True))
+    o2.prefill(K, V, init_score=r.standard_normal((1, 1, N)))
+    expect2 = np.concatenate([np.arange(k), np.sort(np.concatenate([mid[::s], mid[1::s]])), np.arange(N - w, N)])
+    np.testing.assert_array_equal(o2.export()[3][0, 0], expect2)
