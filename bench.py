@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run the library's plain copy kernel once on this many MiB (for rocprofv3 --pmc runs: "
                          "its known size gives the scale of the byte counters)")
+    ap.add_argument("--prefill-obs", type=int, default=0,
+                    help="also time the prefill of one layer with this many observed prompt queries (prefill scoring; "
+                         "off the decode metric) and report it as `prefill_scoring`")
     return ap.parse_args()
 
 
@@ -67,6 +70,35 @@ def run_steps(caches, dec, out, first, count):
         for layer, c in enumerate(caches):
             d = dec[layer % len(dec)]
             c.decode_step(d["q"][t], d["k"][t], d["v"][t], out)
+
+
+def prefill_scoring(wl, cache, n_obs, device, reps=3):
+    """Time of one layer's prefill with and without scoring by the last n_obs prompt queries.  The difference is
+    the two scoring kernels; their work is 2 x 2 D flops per (query, visible key) pair and query head."""
+    import torch
+    from workloads import prompt_inputs
+    p = prompt_inputs(wl.scaled(n_obs=n_obs), device=device)
+    q_obs = p["q_obs"][:, :, p["q_obs"].shape[2] - n_obs:, :].contiguous()
+
+    def timed(q):
+        cache.prefill(p["K"], p["V"], q_obs=q)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            cache.prefill(p["K"], p["V"], q_obs=q)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    with_scoring, without = timed(q_obs), timed(None)
+    N = wl.prompt
+    pairs = n_obs * (N - n_obs) + n_obs * (n_obs + 1) / 2             # causal (query, key) pairs per head
+    flops = 4.0 * wl.head_dim * pairs * wl.batch * wl.n_q_heads
+    dt = max(with_scoring - without, 1e-9)
+    mfma = wl.dtype != "fp32"
+    peak = 2500.0 if mfma else 157.3
+    return {"n_obs": n_obs, "prefill_ms": with_scoring * 1e3, "prefill_without_scoring_ms": without * 1e3,
+            "scoring_ms": dt * 1e3, "flops": flops, "achieved": flops / dt / 1e12, "unit": "TFLOP/s",
+            "bound": "mfma" if mfma else "alu", "peak": peak, "frac": flops / dt / 1e12 / peak}
 
 
 def cpu_baseline(wl, budget_s=20.0):
@@ -183,6 +215,9 @@ def main():
                  "evict_time_over_attn_time": (ev_ms + flush_ms) / attn_ms if attn_ms else 0.0,
                  "step_bytes_over_peak_over_step_time": (algo_bytes / max(launches, 1) * layers / HBM_PEAK_GBS / 1e9)
                                                         / (elapsed / steps)}
+
+    if args.prefill_obs:
+        extra["prefill_scoring"] = prefill_scoring(wl, caches[0], min(args.prefill_obs, wl.prompt), device)
 
     base = None if args.no_cpu_baseline else cpu_baseline(wl)
     line = {

@@ -102,7 +102,11 @@ int make_layout(const buzz_config_t* c, Layout* L)
     L->stScore = take(strows * 4);
     L->stPos = take(strows * 4);
     L->pscore = take((size_t)units * c->max_context * 4);
-    L->obs_stats = take((size_t)units * ceil_div(c->max_context, kObsKeyBlock) * kObsRows * 2 * 4);
+    {   // prefill scoring statistics: what the vector path (fp32) or the matrix-core path (16-bit) needs
+        const size_t vec = (size_t)units * ceil_div(c->max_context, kObsKeyBlock) * kObsRows * 2 * 4;
+        const size_t mma = (size_t)c->batch * c->n_q_heads * kObsPassRows * 2 * 4;
+        L->obs_stats = take(c->kv_dtype == BUZZ_FP32 ? vec : mma);
+    }
     L->total = off;
     return BUZZ_OK;
 }
@@ -391,7 +395,7 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
         if (hipError_t e = launch_fill_f32(ps, init_score, (int64_t)L.units * N, st)) return hip_rc(e);
         if (n_obs > 0) {
             const int G = L.G;
-            const int max_q = kObsRows / G;                // queries per pass
+            const int max_q = obs_pass_queries(cfg.kv_dtype, G);   // queries of one head per pass
             for (int64_t t0 = 0; t0 < n_obs; t0 += max_q) {
                 ObsArgs oa{};
                 oa.K = kp; oa.q_obs = q_obs; oa.score = ps; oa.stats = c->at<float>(L.obs_stats);

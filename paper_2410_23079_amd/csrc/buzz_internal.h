@@ -120,9 +120,10 @@ struct ObsArgs {               // prefill scoring: causal attention of observed 
     const void* K;             // [units][N][D]
     const void* q_obs;         // [B][Hq][n_obs][D]; query t sits at prompt position N - n_obs + t
     float* score;              // [units][N]   accumulated in place
-    float* stats;              // [units][key_blocks][kObsRows][2] per key-block (max, sum) of every query row
+    float* stats;              // vector path: [units][key_blocks][kObsRows][2] per key-block (max, sum) of every query
+                               // row; matrix-core path: [B * Hq][kObsPassRows][2] (max, 1/sum) of every query
     int32_t N, n_obs;
-    int32_t t_begin, t_count;  // queries scored by this pass; t_count * G <= kObsRows
+    int32_t t_begin, t_count;  // queries scored by this pass; at most obs_pass_queries()
     int32_t Hq, Hkv;
     int32_t log_n;             // 1: a query at prompt position i is scaled by log(i + 1) / log(512) (Sec. 3.5)
     float scale_log2;
@@ -130,6 +131,7 @@ struct ObsArgs {               // prefill scoring: causal attention of observed 
 
 constexpr int kObsRows = 256;        // query rows (query x group member) per pass = threads per block
 constexpr int kObsKeyBlock = 1024;   // keys per block of the row-statistics kernel
+constexpr int kObsPassRows = 4096;   // matrix-core scoring: queries per head and pass (stats: [heads][kObsPassRows][2])
 
 // Optional event pair: when both are non-null the launch records the kernel's own begin / end
 // timestamps into them (used by the benchmark profiling pass).
@@ -147,7 +149,8 @@ hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st, T
 hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st, Timing tm = {});
 hipError_t launch_fill_f32(float* dst, const float* src, int64_t n, hipStream_t st);  // src NULL => zeros
 hipError_t launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
-hipError_t launch_obs_scores(int dtype, int D, int G, const ObsArgs& a, int units, hipStream_t st);
+hipError_t launch_obs_scores(int dtype, int D, int G, const ObsArgs& a, int units, hipStream_t st, Timing tm = {});
+int obs_pass_queries(int dtype, int G);   // queries of one head a single scoring pass covers
 int attn_tile_rows(int dtype, int D, int G);   // rows one block consumes per loop trip (split sizes are multiples)
 bool attn_supported(int dtype, int D, int G);
 

@@ -9,8 +9,12 @@
 //                   merges the row statistics, recomputes the logits and adds the column sums of
 //                   the probabilities to the prompt scores.
 // Both form a logit as an fma chain over the head dimension in the same order, so the two passes
-// see identical logits.  Plain fp32 vector arithmetic: this runs once per prompt and is not on the
-// decode path.
+// see identical logits.  Plain fp32 vector arithmetic; used for fp32 caches.
+//
+// 16-bit caches take the matrix-core pair below instead (obs_mfma_kernel<.., 1> and <.., 2>): the same two
+// steps, but q.K^T runs on 16x16x32 MFMA tiles and a pass covers up to kObsPassRows queries per head, so
+// scoring with every prompt query (n_obs = N) costs two launches per 4096 queries instead of two per 256
+// query rows.
 #include "buzz_internal.h"
 
 namespace buzz {
@@ -183,6 +187,220 @@ __global__ __launch_bounds__(256) void obs_col_sums_kernel(const ObsArgs a, cons
     if (j < a.N) a.score[(size_t)unit * a.N + j] += col;
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// Matrix-core prefill scoring (16-bit caches).
+//
+// One template serves both steps.  A wave keeps 64 "stationary" vectors in registers as the B operand of
+// v_mfma_f32_16x16x32 (4 column tiles of 16) and streams tiles of 16 "moving" vectors through the A
+// operand; lane (j, q) = (lane % 16, lane / 16) loads, of vector j of a tile, the 16-byte chunks 4p + q
+// (a permutation of the contraction index that both operands share), and receives the four products of
+// moving vectors 4q .. 4q+3 with stationary vector j.
+//   step 1 (row statistics): stationary = 64 queries of one head, moving = the keys they may see;
+//           every lane keeps a running (max, sum) of its query over its keys; merged over q at the end.
+//   step 2 (column sums):    stationary = 64 keys, moving = the queries that may see them, head after
+//           head of the group; every lane adds exp2(s - max_i) / sum_i of its key over its queries.
+// The four waves of a block take adjacent groups of 64 stationary vectors and stream the same tiles.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT> __device__ inline f32x4 mma16(const uint4& a, const uint4& b, f32x4 c);
+template <> __device__ inline f32x4 mma16<BUZZ_BF16>(const uint4& a, const uint4& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+template <> __device__ inline f32x4 mma16<BUZZ_FP16>(const uint4& a, const uint4& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+constexpr int kMmaCols = 64;            // stationary vectors per wave
+constexpr int kMmaBlockCols = 256;      // ... per block of four waves
+
+template <int DT, int D, int STEP>
+__global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
+{
+    constexpr int ROWB = D * 2, QP = D / 32, CT = kMmaCols / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 15, q = lane >> 4;
+    const int G = a.Hq / a.Hkv;
+    const int t_end = a.t_begin + a.t_count;               // queries [t_begin, t_end) of q_obs are scored by this pass
+    const int shift = a.N - a.n_obs;                       // prompt position of query t is shift + t
+    auto chunk = [&](const char* row, int p) { return *(const uint4*)(row + (4 * p + q) * 16); };
+
+    if constexpr (STEP == 1) {
+        const int head = blockIdx.y;                       // b * Hq + h
+        const int b = head / a.Hq, h = head - b * a.Hq;
+        const int unit = b * a.Hkv + h / G;
+        // the latest queries see the most keys: their blocks go first
+        const int t_base = a.t_begin + ((int)gridDim.x - 1 - (int)blockIdx.x) * kMmaBlockCols + wave * kMmaCols;
+        if (t_base >= t_end) return;
+        const char* Qb = (const char*)a.q_obs + (size_t)head * a.n_obs * ROWB;
+        const char* Kb = (const char*)a.K + (size_t)unit * a.N * ROWB;
+        uint4 qf[CT][QP];
+        int pos[CT];
+        float scale[CT], m[CT], l[CT];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const int t = t_base + 16 * ct + j;
+            pos[ct] = t < t_end ? shift + t : -1;          // -1: no key is visible, the column stays empty
+            scale[ct] = query_scale(a, max(pos[ct], 0));
+            const char* row = Qb + (size_t)min(t, a.n_obs - 1) * ROWB;
+#pragma unroll
+            for (int p = 0; p < QP; ++p) qf[ct][p] = chunk(row, p);
+            m[ct] = -INFINITY; l[ct] = 0.f;
+        }
+        const int k_last = shift + min(t_base + kMmaCols, t_end) - 1;   // the wave's latest query sees keys 0 .. k_last
+        const int k_free = shift + t_base;                 // keys up to here are visible to every query of the wave
+        auto load_keys = [&](uint4 (&kf)[QP], int k0) {
+            const char* row = Kb + (size_t)min(k0 + j, a.N - 1) * ROWB;
+#pragma unroll
+            for (int p = 0; p < QP; ++p) kf[p] = chunk(row, p);
+        };
+        auto consume = [&](const uint4 (&kf)[QP], int k0) {
+            const bool masked = k0 + 15 > k_free || t_base + kMmaCols > t_end;   // wave-uniform
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int p = 0; p < QP; ++p) acc = mma16<DT>(kf[p], qf[ct][p], acc);
+                float sv[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {              // causal: key k0 + 4q + v against this lane's query
+                    sv[v] = acc[v] * scale[ct];
+                    if (masked && k0 + 4 * q + v > pos[ct]) sv[v] = -INFINITY;
+                }
+                const float mn = fmaxf(fmaxf(m[ct], fmaxf(sv[0], sv[1])), fmaxf(sv[2], sv[3]));
+                const float mref = mn == -INFINITY ? 0.f : mn;
+                float sum = 0.f;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f(sv[v] - mref);
+                l[ct] = fmaf(l[ct], __builtin_amdgcn_exp2f(m[ct] - mref), sum);
+                m[ct] = mn;
+            }
+        };
+        uint4 ka[QP], kb[QP];                              // two tile buffers: the next tile is requested first
+        load_keys(ka, 0);
+        for (int k0 = 0; k0 <= k_last; k0 += 32) {
+            if (k0 + 16 <= k_last) load_keys(kb, k0 + 16);
+            consume(ka, k0);
+            if (k0 + 16 > k_last) break;
+            if (k0 + 32 <= k_last) load_keys(ka, k0 + 32);
+            consume(kb, k0 + 16);
+        }
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {                  // merge the four key subsets of a query
+#pragma unroll
+            for (int off = 16; off < 64; off <<= 1) {
+                const float mo = __shfl_xor(m[ct], off), lo = __shfl_xor(l[ct], off);
+                const float mn = fmaxf(m[ct], mo);
+                const float mref = mn == -INFINITY ? 0.f : mn;
+                l[ct] = l[ct] * __builtin_amdgcn_exp2f(m[ct] - mref) + lo * __builtin_amdgcn_exp2f(mo - mref);
+                m[ct] = mn;
+            }
+            const int t = t_base + 16 * ct + j;
+            if (q == 0 && t < t_end) {
+                float* st = a.stats + ((size_t)head * kObsPassRows + (t - a.t_begin)) * 2;
+                st[0] = m[ct];
+                st[1] = 1.0f / l[ct];                      // key 0 is visible to every query: l > 0
+            }
+        }
+    } else {
+        const int unit = blockIdx.y;
+        const int b = unit / a.Hkv, kvh = unit - b * a.Hkv;
+        const int j_base = blockIdx.x * kMmaBlockCols + wave * kMmaCols;
+        if (j_base >= a.N) return;
+        const char* Kb = (const char*)a.K + (size_t)unit * a.N * ROWB;
+        uint4 kf[CT][QP];
+        float col[CT];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const char* row = Kb + (size_t)min(j_base + 16 * ct + j, a.N - 1) * ROWB;
+#pragma unroll
+            for (int p = 0; p < QP; ++p) kf[ct][p] = chunk(row, p);
+            col[ct] = 0.f;
+        }
+        // the first query that sees key j_base, on the tile grid anchored at t_begin
+        const int t_first = max(j_base - shift, a.t_begin);
+        const int t_lo = a.t_begin + ((t_first - a.t_begin) & ~15);
+        for (int g = 0; g < G; ++g) {
+            const int head = b * a.Hq + kvh * G + g;
+            const char* Qb = (const char*)a.q_obs + (size_t)head * a.n_obs * ROWB;
+            const float* st = a.stats + (size_t)head * kObsPassRows * 2;
+            struct Moving { uint4 qf[QP]; float2 st[4]; };
+            auto load_queries = [&](Moving& mv, int t0) {
+                const char* row = Qb + (size_t)min(t0 + j, a.n_obs - 1) * ROWB;
+#pragma unroll
+                for (int p = 0; p < QP; ++p) mv.qf[p] = chunk(row, p);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)                // statistics of moving queries 4q .. 4q+3
+                    mv.st[v] = *(const float2*)(st + (size_t)(min(t0 + 4 * q + v, t_end - 1) - a.t_begin) * 2);
+            };
+            auto consume = [&](const Moving& mv, int t0) {
+                // wave-uniform: every query of the tile exists and sees every key of the wave
+                const bool masked = t0 + 16 > t_end || shift + t0 < j_base + kMmaCols - 1;
+                float sc[4];
+                int posq[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int t = t0 + 4 * q + v;
+                    posq[v] = t < t_end ? shift + t : -1;
+                    sc[v] = query_scale(a, max(posq[v], 0));
+                }
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int p = 0; p < QP; ++p) acc = mma16<DT>(mv.qf[p], kf[ct][p], acc);
+                    const int key = j_base + 16 * ct + j;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float e = __builtin_amdgcn_exp2f(fmaf(acc[v], sc[v], -mv.st[v].x));
+                        if (masked && key > posq[v]) e = 0.f;
+                        col[ct] = fmaf(e, mv.st[v].y, col[ct]);
+                    }
+                }
+            };
+            Moving ma, mb;                                 // two tile buffers
+            if (t_lo < t_end) load_queries(ma, t_lo);
+            for (int t0 = t_lo; t0 < t_end; t0 += 32) {
+                if (t0 + 16 < t_end) load_queries(mb, t0 + 16);
+                consume(ma, t0);
+                if (t0 + 16 >= t_end) break;
+                if (t0 + 32 < t_end) load_queries(ma, t0 + 32);
+                consume(mb, t0 + 16);
+            }
+        }
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            float c = col[ct] + __shfl_xor(col[ct], 16);
+            c += __shfl_xor(c, 32);
+            const int key = j_base + 16 * ct + j;
+            if (q == 0 && key < a.N) a.score[(size_t)unit * a.N + key] += c;
+        }
+    }
+}
+
+template <int DT, int D>
+hipError_t launch_obs_mfma_t(const ObsArgs& a, int units, hipStream_t st, Timing tm)
+{
+    const int heads = units / a.Hkv * a.Hq;
+    BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 1>), dim3((a.t_count + kMmaBlockCols - 1) / kMmaBlockCols, heads), dim3(256), 0, st, tm, a);
+    if (hipError_t e = hipGetLastError()) return e;
+    BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 2>), dim3((a.N + kMmaBlockCols - 1) / kMmaBlockCols, units), dim3(256), 0, st, tm, a);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_obs_mfma_d(int D, const ObsArgs& a, int units, hipStream_t st, Timing tm)
+{
+    switch (D) {
+        case 64: return launch_obs_mfma_t<DT, 64>(a, units, st, tm);
+        case 128: return launch_obs_mfma_t<DT, 128>(a, units, st, tm);
+        case 256: return launch_obs_mfma_t<DT, 256>(a, units, st, tm);
+    }
+    return hipErrorInvalidValue;
+}
+
 template <int DT, int D>
 hipError_t launch_obs_t(const ObsArgs& a, int units, hipStream_t st)
 {
@@ -206,13 +424,18 @@ hipError_t launch_obs_d(int D, const ObsArgs& a, int units, hipStream_t st)
 
 }  // namespace
 
-hipError_t launch_obs_scores(int dtype, int D, int /*G*/, const ObsArgs& a, int units, hipStream_t st)
+int obs_pass_queries(int dtype, int G)
+{
+    return dtype == BUZZ_FP32 ? kObsRows / G : kObsPassRows;
+}
+
+hipError_t launch_obs_scores(int dtype, int D, int /*G*/, const ObsArgs& a, int units, hipStream_t st, Timing tm)
 {
     if (a.N <= 0 || a.t_count <= 0) return hipSuccess;
     switch (dtype) {
         case BUZZ_FP32: return launch_obs_d<BUZZ_FP32>(D, a, units, st);
-        case BUZZ_FP16: return launch_obs_d<BUZZ_FP16>(D, a, units, st);
-        case BUZZ_BF16: return launch_obs_d<BUZZ_BF16>(D, a, units, st);
+        case BUZZ_FP16: return launch_obs_mfma_d<BUZZ_FP16>(D, a, units, st, tm);
+        case BUZZ_BF16: return launch_obs_mfma_d<BUZZ_BF16>(D, a, units, st, tm);
     }
     return hipErrorInvalidValue;
 }

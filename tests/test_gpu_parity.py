@@ -108,6 +108,14 @@ def test_more_units_than_compute_units(deterministic):
     assert st["evictions"] == 5
 
 
+@pytest.mark.parametrize("dtype,G", [("bf16", 1), ("fp16", 2)])
+def test_prefill_scores_from_every_prompt_query(dtype, G):
+    """n_obs = N (H2O-style prompt scores) beyond one scoring pass of 4096 queries, ragged tiles everywhere."""
+    wl = small(batch=1, n_kv_heads=2, n_q_heads=2 * G, head_dim=64, dtype=dtype, prompt=4500, decode_steps=8,
+               sink=4, window=700, segment=32, keep=3, evict_every=8, n_obs=4500)
+    run(wl, units=[(0, 1)])
+
+
 # ------------------------------------------------------------------ degenerate cases of the method
 def test_keep_zero_streaming():
     run(small(prompt=200, decode_steps=40, keep=0, n_obs=8))
