@@ -1036,7 +1036,7 @@ int attn_tile_rows(int dtype, int D, int G)
     if (G >= 2 && dtype != BUZZ_FP32) return 16;          // matrix-core kernel: 16-row tiles
     int u = G == 1 ? BUZZ_U_G1 : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
     if (u * rpw < 4) u = 4 / rpw;
-    return 4 * rpw * u;
+    return rpw * u;                                       // rows of one wave-wide trip
 }
 
 hipError_t launch_attn_split(int dtype, int D, int G, const AttnArgs& a, int units, hipStream_t st, Timing tm)
