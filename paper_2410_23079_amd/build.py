@@ -11,7 +11,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbuzz.so")
 # (source, object stem, extra defines); the attention kernels are one translation unit per dtype
 SOURCES = [("buzz_api.cpp", "buzz_api", []), ("evict_kernels.hip", "evict_kernels", []),
-           ("prefill_kernels.hip", "prefill_kernels", []),
+           # matrix-core results go to ordinary registers: the scoring kernels read every one of them with
+           # vector instructions, and a copy out of the accumulation registers per element costs 15% of them
+           ("prefill_kernels.hip", "prefill_kernels", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
            ("attn_kernels.hip", "attn_fp32", ["-DBUZZ_TU=0"]), ("attn_kernels.hip", "attn_fp16", ["-DBUZZ_TU=1"]),
            ("attn_kernels.hip", "attn_bf16", ["-DBUZZ_TU=2"]), ("attn_kernels.hip", "attn_common", ["-DBUZZ_TU=3"])]
 FLAGS = [

@@ -17,6 +17,8 @@
 // query rows.
 #include "buzz_internal.h"
 
+#include <type_traits>
+
 namespace buzz {
 namespace {
 
@@ -216,9 +218,14 @@ template <> __device__ inline f32x4 mma16<BUZZ_FP16>(const uint4& a, const uint4
 constexpr int kMmaCols = 64;            // stationary vectors per wave
 constexpr int kMmaBlockCols = 256;      // ... per block of four waves
 
-template <int DT, int D, int STEP>
+template <int DT, int D, int STEP, bool LOGN>
 __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
 {
+    // softmax scale (log2 units) of the query at prompt position `pos`; a template flag rather than a
+    // run-time one: as a run-time select the logarithm would be evaluated for every row of every tile
+    auto qscale = [&](int pos) {
+        return LOGN ? a.scale_log2 * (logf((float)(pos + 1)) * (1.0f / 6.2383246250395077f)) : a.scale_log2;
+    };
     constexpr int ROWB = D * 2, QP = D / 32, CT = kMmaCols / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 15, q = lane >> 4;
@@ -228,11 +235,12 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
     auto chunk = [&](const char* row, int p) { return *(const uint4*)(row + (4 * p + q) * 16); };
 
     if constexpr (STEP == 1) {
-        const int head = blockIdx.y;                       // b * Hq + h
+        const int head = blockIdx.x;                       // b * Hq + h
         const int b = head / a.Hq, h = head - b * a.Hq;
         const int unit = b * a.Hkv + h / G;
-        // the latest queries see the most keys: their blocks go first
-        const int t_base = a.t_begin + ((int)gridDim.x - 1 - (int)blockIdx.x) * kMmaBlockCols + wave * kMmaCols;
+        // the latest queries see the most keys: their blocks go first, for all heads, so that the launch
+        // ends with the short blocks (blockIdx.x, which the dispatcher advances first, is the head)
+        const int t_base = a.t_begin + ((int)gridDim.y - 1 - (int)blockIdx.y) * kMmaBlockCols + wave * kMmaCols;
         if (t_base >= t_end) return;
         const char* Qb = (const char*)a.q_obs + (size_t)head * a.n_obs * ROWB;
         const char* Kb = (const char*)a.K + (size_t)unit * a.N * ROWB;
@@ -243,7 +251,7 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
         for (int ct = 0; ct < CT; ++ct) {
             const int t = t_base + 16 * ct + j;
             pos[ct] = t < t_end ? shift + t : -1;          // -1: no key is visible, the column stays empty
-            scale[ct] = query_scale(a, max(pos[ct], 0));
+            scale[ct] = qscale(max(pos[ct], 0));
             const char* row = Qb + (size_t)min(t, a.n_obs - 1) * ROWB;
 #pragma unroll
             for (int p = 0; p < QP; ++p) qf[ct][p] = chunk(row, p);
@@ -256,8 +264,10 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
 #pragma unroll
             for (int p = 0; p < QP; ++p) kf[p] = chunk(row, p);
         };
-        auto consume = [&](const uint4 (&kf)[QP], int k0) {
-            const bool masked = k0 + 15 > k_free || t_base + kMmaCols > t_end;   // wave-uniform
+        // m[] holds the running maximum of the RAW products (the scale of a query is a positive constant, so
+        // the order is the same) and the scale enters through one fma per element: exp2(s * scale - m * scale)
+        auto consume_as = [&](const uint4 (&kf)[QP], int k0, auto masked_tag) {
+            constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -266,17 +276,25 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
                 float sv[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {              // causal: key k0 + 4q + v against this lane's query
-                    sv[v] = acc[v] * scale[ct];
-                    if (masked && k0 + 4 * q + v > pos[ct]) sv[v] = -INFINITY;
+                    sv[v] = acc[v];
+                    if (MASKED && k0 + 4 * q + v > pos[ct]) sv[v] = -INFINITY;
                 }
                 const float mn = fmaxf(fmaxf(m[ct], fmaxf(sv[0], sv[1])), fmaxf(sv[2], sv[3]));
-                const float mref = mn == -INFINITY ? 0.f : mn;
+                const float mref = (MASKED && mn == -INFINITY) ? 0.f : mn;
+                const float off = -mref * scale[ct];
                 float sum = 0.f;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f(sv[v] - mref);
-                l[ct] = fmaf(l[ct], __builtin_amdgcn_exp2f(m[ct] - mref), sum);
+                for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f(fmaf(sv[v], scale[ct], off));
+                // (the rescale factor must be exactly 1 while the maximum stands still: an fma against the
+                // rounded offset would leave a residual of the same sign tile after tile)
+                l[ct] = fmaf(l[ct], __builtin_amdgcn_exp2f((m[ct] - mref) * scale[ct]), sum);
                 m[ct] = mn;
             }
+        };
+        auto consume = [&](const uint4 (&kf)[QP], int k0) {
+            // wave-uniform: does a causal boundary or the end of the query list cross this tile?
+            if (k0 + 15 > k_free || t_base + kMmaCols > t_end) consume_as(kf, k0, std::true_type{});
+            else consume_as(kf, k0, std::false_type{});
         };
         uint4 ka[QP], kb[QP];                              // two tile buffers: the next tile is requested first
         load_keys(ka, 0);
@@ -294,20 +312,21 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
                 const float mo = __shfl_xor(m[ct], off), lo = __shfl_xor(l[ct], off);
                 const float mn = fmaxf(m[ct], mo);
                 const float mref = mn == -INFINITY ? 0.f : mn;
-                l[ct] = l[ct] * __builtin_amdgcn_exp2f(m[ct] - mref) + lo * __builtin_amdgcn_exp2f(mo - mref);
+                l[ct] = l[ct] * __builtin_amdgcn_exp2f((m[ct] - mref) * scale[ct]) +
+                        lo * __builtin_amdgcn_exp2f((mo - mref) * scale[ct]);
                 m[ct] = mn;
             }
             const int t = t_base + 16 * ct + j;
             if (q == 0 && t < t_end) {
                 float* st = a.stats + ((size_t)head * kObsPassRows + (t - a.t_begin)) * 2;
-                st[0] = m[ct];
+                st[0] = m[ct] * scale[ct];                // maximum of the scaled logits
                 st[1] = 1.0f / l[ct];                      // key 0 is visible to every query: l > 0
             }
         }
     } else {
-        const int unit = blockIdx.y;
+        const int unit = blockIdx.x;                       // the earliest keys are seen by the most queries: they go first
         const int b = unit / a.Hkv, kvh = unit - b * a.Hkv;
-        const int j_base = blockIdx.x * kMmaBlockCols + wave * kMmaCols;
+        const int j_base = blockIdx.y * kMmaBlockCols + wave * kMmaCols;
         if (j_base >= a.N) return;
         const char* Kb = (const char*)a.K + (size_t)unit * a.N * ROWB;
         uint4 kf[CT][QP];
@@ -335,16 +354,15 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
                 for (int v = 0; v < 4; ++v)                // statistics of moving queries 4q .. 4q+3
                     mv.st[v] = *(const float2*)(st + (size_t)(min(t0 + 4 * q + v, t_end - 1) - a.t_begin) * 2);
             };
-            auto consume = [&](const Moving& mv, int t0) {
-                // wave-uniform: every query of the tile exists and sees every key of the wave
-                const bool masked = t0 + 16 > t_end || shift + t0 < j_base + kMmaCols - 1;
+            auto consume_as = [&](const Moving& mv, int t0, auto masked_tag) {
+                constexpr bool MASKED = decltype(masked_tag)::value;
                 float sc[4];
                 int posq[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int t = t0 + 4 * q + v;
-                    posq[v] = t < t_end ? shift + t : -1;
-                    sc[v] = query_scale(a, max(posq[v], 0));
+                    posq[v] = (!MASKED || t < t_end) ? shift + t : -1;
+                    sc[v] = qscale(max(posq[v], 0));
                 }
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) {
@@ -355,10 +373,15 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         float e = __builtin_amdgcn_exp2f(fmaf(acc[v], sc[v], -mv.st[v].x));
-                        if (masked && key > posq[v]) e = 0.f;
+                        if (MASKED && key > posq[v]) e = 0.f;
                         col[ct] = fmaf(e, mv.st[v].y, col[ct]);
                     }
                 }
+            };
+            auto consume = [&](const Moving& mv, int t0) {
+                // wave-uniform: unmasked if every query of the tile exists and sees every key of the wave
+                if (t0 + 16 > t_end || shift + t0 < j_base + kMmaCols - 1) consume_as(mv, t0, std::true_type{});
+                else consume_as(mv, t0, std::false_type{});
             };
             Moving ma, mb;                                 // two tile buffers
             if (t_lo < t_end) load_queries(ma, t_lo);
@@ -384,9 +407,12 @@ template <int DT, int D>
 hipError_t launch_obs_mfma_t(const ObsArgs& a, int units, hipStream_t st, Timing tm)
 {
     const int heads = units / a.Hkv * a.Hq;
-    BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 1>), dim3((a.t_count + kMmaBlockCols - 1) / kMmaBlockCols, heads), dim3(256), 0, st, tm, a);
+    const dim3 g1(heads, (a.t_count + kMmaBlockCols - 1) / kMmaBlockCols), g2(units, (a.N + kMmaBlockCols - 1) / kMmaBlockCols);
+    if (a.log_n) BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 1, true>), g1, dim3(256), 0, st, tm, a);
+    else BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 1, false>), g1, dim3(256), 0, st, tm, a);
     if (hipError_t e = hipGetLastError()) return e;
-    BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 2>), dim3((a.N + kMmaBlockCols - 1) / kMmaBlockCols, units), dim3(256), 0, st, tm, a);
+    if (a.log_n) BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 2, true>), g2, dim3(256), 0, st, tm, a);
+    else BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 2, false>), g2, dim3(256), 0, st, tm, a);
     return hipGetLastError();
 }
 
