@@ -41,12 +41,12 @@ def parse():
 
 
 def make_caches(wl, layers, max_context, splits, flags):
-    from paper_2410_23079_amd import BuzzCache, BuzzConfig
+    from paper_2410_23079_amd import FLAG_THRESHOLD_TOTAL, BuzzCache, BuzzConfig
     caches = []
     for _ in range(layers):
         c = BuzzCache(BuzzConfig(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.sink, wl.window,
                                  wl.segment, wl.keep, wl.evict_every, max_context, old_stride=wl.old_stride,
-                                 flags=flags))
+                                 flags=flags | (FLAG_THRESHOLD_TOTAL if wl.threshold_total else 0)))
         if splits:
             c.set_splits(splits)
         caches.append(c)
@@ -115,7 +115,8 @@ def cpu_baseline(wl, budget_s=20.0):
     steps = sub.decode_steps
     d = decode_inputs(sub, device="cpu", steps=steps)
     o = OracleCache(OracleConfig(sub.batch, sub.n_q_heads, sub.n_kv_heads, sub.head_dim, sub.sink, sub.window,
-                                 sub.segment, sub.keep, sub.evict_every, sub.old_stride))
+                                 sub.segment, sub.keep, sub.evict_every, sub.old_stride,
+                                 threshold_total=sub.threshold_total))
     o.prefill(p["K"].double().numpy(), p["V"].double().numpy())
     del p
     q, k, v = (d[x].double().numpy() for x in ("q", "k", "v"))
@@ -228,7 +229,7 @@ def main():
         "config": {"workload": wl.name, "layers": layers, "batch": wl.batch, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "prompt": wl.prompt, "sink": wl.sink,
                    "window": wl.window, "segment": wl.segment, "keep": wl.keep, "evict_every": wl.evict_every,
-                   "old_stride": wl.old_stride, "retained_rows_end": n_end, "splits": args.splits or "auto",
+                   "old_stride": wl.old_stride, "threshold_total": wl.threshold_total, "retained_rows_end": n_end, "splits": args.splits or "auto",
                    "kv_loads": "streaming" if args.streaming else "auto"},
         "roofline": roofline, "cpu_baseline": base,
     }

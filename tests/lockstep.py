@@ -76,7 +76,7 @@ def gpu_prompt_scores(wl: Workload, prompt, n_obs: int, flags: int = 0):
 
 
 def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=None, splits=0,
-                 check_auto=True, capacity=0, log_n=False, threshold_total=False, deterministic=True,
+                 check_auto=True, capacity=0, log_n=False, threshold_total=None, deterministic=True,
                  interval_new=False):
     """Returns a dict of the worst errors seen; raises AssertionError on any parity failure."""
     G, D = wl.group, wl.head_dim
@@ -89,6 +89,8 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
     uidx_b = torch.tensor([b for b, _ in units])
     uidx_h = torch.tensor([h for _, h in units])
     stats = dict(out=0.0, score=0.0, prefill_score=0.0, evictions=0)
+    if threshold_total is None:
+        threshold_total = wl.threshold_total
     vflags = ((FLAG_LOG_N if log_n else 0) | (FLAG_THRESHOLD_TOTAL if threshold_total else 0)
               | (FLAG_DETERMINISTIC if deterministic else 0) | (FLAG_INTERVAL_NEW if interval_new else 0))
     okw = dict(log_n=log_n, threshold_total=threshold_total, interval_new=interval_new)
@@ -174,3 +176,57 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
         auto.close()
     gpu.close()
     return stats
+
+
+def run_free(wl: Workload, prompt, decode, units=None, steps=None):
+    """Free run: GPU (fp32 scores) and oracle (fp64 scores) each evict on their OWN accumulated scores.
+
+    Both start from the same prompt scores.  At every eviction the retained position sets are compared; the
+    first difference must be a near-tie: every row one side kept and the other did not has, in the oracle's
+    scores, a counterpart on the other side within a relative gap of 1e-5.  Returns a dict with the number of
+    evictions that agreed and, if the runs parted, the largest gap found at the parting eviction."""
+    G, D = wl.group, wl.head_dim
+    N = prompt["K"].shape[2]
+    steps = wl.decode_steps if steps is None else steps
+    if units is None:
+        units = [(b, h) for b in range(wl.batch) for h in range(wl.n_kv_heads)]
+    U = len(units)
+    uidx_b = torch.tensor([b for b, _ in units]); uidx_h = torch.tensor([h for _, h in units])
+    n_obs = min(wl.n_obs, N)
+    ps = gpu_prompt_scores(wl, prompt, n_obs)
+    gpu = BuzzCache(buzz_config(wl, flags=FLAG_THRESHOLD_TOTAL if wl.threshold_total else 0, max_context=N + steps))
+    gpu.prefill(prompt["K"], prompt["V"], init_score=ps)
+    ora = OracleCache(oracle_config(wl, U, threshold_total=wl.threshold_total))
+    ora.prefill(unit_slices(prompt["K"], units, 1)[:, 0][:, None], unit_slices(prompt["V"], units, 1)[:, 0][:, None],
+                init_score=ps[uidx_b, uidx_h].double().cpu().numpy()[:, None, :])
+    out = torch.empty(wl.batch, wl.n_q_heads, D, dtype=torch.float32, device=prompt["K"].device)
+    res = dict(agreed=0, parted_at=None, gap=0.0)
+    for t in range(steps):
+        q, k, v = decode["q"][t], decode["k"][t], decode["v"][t]
+        gpu.decode_step(q, k, v, out)
+        ora.decode_step(unit_slices(q, units, G), unit_slices(k, units, 1), unit_slices(v, units, 1))
+        _, n_old_now, new_now = gpu.lengths()
+        if (n_old_now + new_now if wl.threshold_total else new_now) < wl.evict_every:
+            continue
+        _, _, A_before, P_before = ora.export()
+        gpu.evict()
+        ora.evict()
+        Pg = gpu.export()[3][uidx_b, uidx_h].cpu().numpy()
+        Po = ora.export()[3][:, 0]
+        if (Pg == Po).all():
+            res["agreed"] += 1
+            continue
+        res["parted_at"] = t
+        for u in range(U):                                   # every one-sided row needs a near-tied counterpart
+            score_of = dict(zip(P_before[u, 0].tolist(), A_before[u, 0].tolist()))
+            g_only = sorted(set(Pg[u].tolist()) - set(Po[u].tolist()))
+            o_only = sorted(set(Po[u].tolist()) - set(Pg[u].tolist()))
+            assert len(g_only) == len(o_only), "the two runs kept different numbers of rows"
+            for a_pos, b_pos in zip(g_only, o_only):         # same segment, in order
+                sa, sb = score_of[a_pos], score_of[b_pos]
+                gap = abs(sa - sb) / max(abs(sa), abs(sb), 1e-30)
+                res["gap"] = max(res["gap"], gap)
+                assert gap <= 1e-5, f"step {t}: rows {a_pos} / {b_pos} differ by {gap:.2e}, not a near-tie"
+        break
+    gpu.close()
+    return res

@@ -151,11 +151,15 @@ def test_dry_run_sizes_match_closed_form_and_oracle(seed):
 def test_dry_run_benchmark_configs_match_the_sizes_in_the_scope_table():
     from workloads import WORKLOADS
     expect = {"tiny": (96, 112), "llama7b_layer": (1412, 1476), "llama7b_full": (3844, 3876),
-              "gqa8b_layer": (7684, 7716), "long131k": (23556, 23572)}
+              "gqa8b_layer": (7684, 7716), "long131k": (23556, 23572),
+              # paper parameters: 3836 prompt tokens -> ceil(3836/5) = 768 old; evictions at steps 341 (768 -> 256
+              # old, 341 -> 69 new) and 1125 (325 -> 109, 784 -> 157); 411 tokens buffered at the end
+              "llama7b_layer_paper": (4 + 768 + 256, 4 + 266 + 411 + 256)}
+    from paper_2410_23079_amd import FLAG_THRESHOLD_TOTAL
     for name, wl in WORKLOADS.items():
         g = BuzzCache(BuzzConfig(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.sink, wl.window,
                                  wl.segment, wl.keep, wl.evict_every, wl.max_context, old_stride=wl.old_stride,
-                                 flags=DRY))
+                                 flags=DRY | (FLAG_THRESHOLD_TOTAL if wl.threshold_total else 0)))
         g.prefill(None, None, n_prompt=wl.prompt)
         a = g.lengths()[0]
         for _ in range(wl.decode_steps):

@@ -1,4 +1,4 @@
-"""The five benchmark / parity workloads: shapes, dtypes, cache parameters, value recipe."""
+"""The benchmark / parity workloads: shapes, dtypes, cache parameters, value recipe."""
 from __future__ import annotations
 
 from dataclasses import dataclass, replace
@@ -7,7 +7,7 @@ from dataclasses import dataclass, replace
 @dataclass(frozen=True)
 class Workload:
     name: str
-    index: int            # 1..5, enters the seed
+    index: int            # 1..6, enters the seed
     layers: int
     batch: int
     n_q_heads: int
@@ -27,6 +27,7 @@ class Workload:
     planted_frac: float = 0.0      # fraction of prompt keys that get +3u (u shared with queries)
     clusters: int = 0              # >0: keys/queries drawn around this many topic means per head
     cluster_noise: float = 0.3
+    threshold_total: bool = False  # T bounds old + new tokens (the reading of the Parameter Estimation theorem)
 
     @property
     def group(self) -> int:
@@ -52,6 +53,11 @@ WORKLOADS = {
                             key_scale_sigma=0.5),
     "long131k": Workload("long131k", 5, 1, 1, 32, 32, 128, "bf16", 131072, 128, 4, 8192, 128, 16, 128, 1, 256,
                          clusters=50),
+    # The paper's own parameterisation on config 2's shape: stride 5, old tokens re-sampled with
+    # s^ = floor((s+1)/2) = 3 at every eviction, T bounding old + new tokens and set by the Parameter
+    # Estimation theorem (T / w = 26/6 = 4.33 for s = 5, w = 256), one survivor per segment.
+    "llama7b_layer_paper": Workload("llama7b_layer_paper", 6, 1, 8, 32, 32, 128, "fp16", 4096, 1536, 4, 256, 5, 1,
+                                    1109, 0, 256, key_scale_sigma=0.5, threshold_total=True),
 }
 
 
