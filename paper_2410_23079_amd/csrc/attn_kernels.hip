@@ -34,8 +34,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // Build-time tuning knobs (defaults are the measured best; a sweep overrides them with -D).
+// 16-byte loads of K (and of V) per lane and tile.  Group size 1 keeps two tiles in flight; small tiles win
+// there because the waves claim them dynamically (finer balance): 2 loads when the cache streams from HBM
+// (4: -2%, 1: -9%, too little in flight), 1 load when it is served by the last-level cache (+3.5% over 2).
 #ifndef BUZZ_U_G1
-#define BUZZ_U_G1 4      // 16-byte loads of K (and of V) per lane and tile, group size 1 (two tiles in flight)
+#define BUZZ_U_G1 2
+#endif
+#ifndef BUZZ_U_G1_CACHED
+#define BUZZ_U_G1_CACHED 1
 #endif
 #ifndef BUZZ_U_G2
 #define BUZZ_U_G2 4
@@ -943,7 +949,10 @@ __global__ __launch_bounds__(256) void flush_scores_kernel(const AttnArgs a)
     }
 }
 
-template <int G> constexpr int unroll_for() { return G == 1 ? BUZZ_U_G1 : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8)); }
+template <int G, bool NT> constexpr int unroll_for()
+{
+    return G == 1 ? (NT ? BUZZ_U_G1 : BUZZ_U_G1_CACHED) : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
+}
 
 template <typename T, int D, int G>
 hipError_t launch_split_t(const AttnArgs& a, int units, hipStream_t st, Timing tm)
@@ -961,13 +970,15 @@ hipError_t launch_split_t(const AttnArgs& a, int units, hipStream_t st, Timing t
         return hipGetLastError();
     } else {
         constexpr int RPW = 64 / (D / Elem<T>::VEC);
-        constexpr int U = unroll_for<G>() * RPW >= 4 ? unroll_for<G>() : 4 / RPW;   // a trip covers at least 4 rows
+        // a trip covers at least 4 rows
+        constexpr int US = unroll_for<G, true>() * RPW >= 4 ? unroll_for<G, true>() : 4 / RPW;     // streaming loads
+        constexpr int UC = unroll_for<G, false>() * RPW >= 4 ? unroll_for<G, false>() : 4 / RPW;   // cached loads
         if (a.waves == 8) {
-            if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, true, 8>), grid, block, lds, st, tm, a);
-            else BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, false, 8>), grid, block, lds, st, tm, a);
+            if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, US, true, 8>), grid, block, lds, st, tm, a);
+            else BUZZ_LAUNCH((attn_split_kernel<T, D, G, UC, false, 8>), grid, block, lds, st, tm, a);
         } else {
-            if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, true, 4>), grid, block, lds, st, tm, a);
-            else BUZZ_LAUNCH((attn_split_kernel<T, D, G, U, false, 4>), grid, block, lds, st, tm, a);
+            if (a.streaming) BUZZ_LAUNCH((attn_split_kernel<T, D, G, US, true, 4>), grid, block, lds, st, tm, a);
+            else BUZZ_LAUNCH((attn_split_kernel<T, D, G, UC, false, 4>), grid, block, lds, st, tm, a);
         }
         return hipGetLastError();
     }
@@ -1034,7 +1045,7 @@ int attn_tile_rows(int dtype, int D, int G)
     const int vec = dtype == BUZZ_FP32 ? 4 : 8;
     const int rpw = 64 / (D / vec);
     if (G >= 2 && dtype != BUZZ_FP32) return 16;          // matrix-core kernel: 16-row tiles
-    int u = G == 1 ? BUZZ_U_G1 : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
+    int u = G == 1 ? BUZZ_U_G1_CACHED : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
     if (u * rpw < 4) u = 4 / rpw;
     return rpw * u;                                       // rows of one wave-wide trip
 }
