@@ -502,6 +502,8 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         // merged across blocks at all.
         const int cus = compute_units();
         int64_t S = c->user_splits > 0 ? c->user_splits : (L.units >= cus ? 1 : cus / L.units);
+        // a split of fewer than kMinSplitRows rows costs more in merge latency than it saves in streaming
+        if (c->user_splits == 0 && S > ceil_div(n, kMinSplitRows)) S = ceil_div(n, kMinSplitRows);
         if (S < 1) S = 1;
         if (S > L.s_cap) S = L.s_cap;
         int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
