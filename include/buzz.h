@@ -152,7 +152,7 @@ int buzz_decode_step(buzz_cache_t* cache, const void* q, const void* k_new, cons
                      float* out, void* hip_stream);
 
 /*
- * One eviction (Alg. 1 lines 13-19 with Alg. 2): old rows are interval-sampled
+ * One eviction (the eviction branch of Alg. 1, with Alg. 2): old rows are interval-sampled
  * with stride s^, the rows between old region and window are cut into
  * segments of s from their start (the last may be ragged) and the top
  * min(keep, len) of each segment under (score descending, index ascending;
@@ -200,7 +200,7 @@ int buzz_cache_set_splits(buzz_cache_t* cache, int32_t n_splits);
  */
 typedef struct buzz_profile {
     int64_t attn_launches;     /* split decode-attention kernel */
-    int64_t epilogue_launches; /* combine + score-accumulate kernel */
+    int64_t epilogue_launches; /* score flush kernel (pending score update applied before an eviction or export) */
     int64_t evictions;         /* whole evictions (all their kernels) */
     double attn_ms, epilogue_ms, evict_ms; /* summed device time */
     double attn_row_bytes;     /* sum over attn launches of units * rows * 2 * head_dim * sizeof(element) */

@@ -155,7 +155,7 @@ static int ranks_before(double sa, int64_t ia, double sb, int64_t ib)
     return ia < ib;
 }
 
-/* Alg. 1 lines 13-15 and 19 plus Alg. 2, on one unit. */
+/* The eviction branch of Alg. 1 (split, sample both parts, concatenate) plus Alg. 2, on one unit. */
 static int unit_evict(const oracle_config *c, unit_t *x)
 {
     const int64_t k = c->sink, w = c->window, s = c->segment, D = c->head_dim;

@@ -236,7 +236,7 @@ int flush_scores(buzz_cache_t* c, hipStream_t st)
     return BUZZ_OK;
 }
 
-// Alg. 1 lines 13-19 on the current state.
+// The eviction branch of Alg. 1 on the current state.
 int evict_impl(buzz_cache_t* c, hipStream_t st)
 {
     const buzz_config_t& cfg = c->cfg;

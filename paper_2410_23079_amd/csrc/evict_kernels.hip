@@ -1,4 +1,4 @@
-// BeeHive eviction kernels (Sec. 3.3; Alg. 1 lines 13-19, Alg. 2):
+// BeeHive eviction kernels (Sec. 3.3; the eviction branch of Alg. 1, Alg. 2):
 //   segment_topk : one wavefront per (segment, unit) ranks the segment's accumulated scores and
 //                  emits the top min(keep, len) rows in index order (ties -> lowest index, NaN lowest);
 //   gather_rows  : packs K, V, score and position of selected rows into their destination
