@@ -2,10 +2,11 @@
 // the append of eq. 2, the split-softmax attention, the merge of the splits and the accumulated-score
 // update ("A" of Alg. 2) all happen inside attn_split.
 //
-//  - One block per (key-range split, unit).  A wave reads 64 x 16 B per load instruction = RPW
-//    consecutive cache rows, LPR = 64 / RPW lanes per row: every load is one contiguous 1 KB burst.
-//    q.k is a two-element-dot chain per lane plus an LPR-lane DPP reduction; softmax runs online per
-//    lane group; p.V accumulates in registers.
+//  - One block per (key-range split, unit).  Two streaming variants: on the vector ALU a wave reads
+//    64 x 16 B per load instruction = RPW consecutive cache rows, LPR = 64 / RPW lanes per row (every
+//    load is one contiguous 1 KB burst), q.k is a two-element-dot chain per lane plus an LPR-lane DPP
+//    reduction, softmax runs online per lane group and p.V accumulates in registers; with several
+//    query heads per kv head on a 16-bit cache both contractions run on the matrix cores instead.
 //  - The scaled logit of every row is written to a scratch array.  A row's probability needs the
 //    maximum and sum over ALL splits, which only exist once the step is over, so the score update of
 //    step t is applied by step t+1 while it streams the same rows anyway (one lane per row, coalesced):
@@ -542,11 +543,12 @@ __global__ __launch_bounds__(NW * 64, BUZZ_MIN_BLOCKS) void attn_split_kernel(co
     }
 
     // Work split inside a block.  A split's logical row range is cut into at most four physically
-    // contiguous runs; inside a run the block's waves take tiles of WROWS rows round-robin, on a grid
-    // anchored at a physical multiple of WROWS (`lead` rows before the run's first row are masked).  The streaming phase only reads: logits are staged in LDS, and all per-row side
-    // traffic (this step's logits out, the previous step's logits and the old score in, the new score out)
-    // happens in one dense phase at the end of the block.  Writes that trickle into a saturated read
-    // stream were measured to cost ~5% of the kernel per 1% of extra bytes.
+    // contiguous runs; inside a run, tiles of WROWS rows sit on a grid anchored at a physical multiple
+    // of WROWS (`lead` rows before the run's first row are masked), and the block's waves take the tiles
+    // of all runs one after another (TileMap).  The streaming phase only reads: logits are staged in LDS,
+    // and all per-row side traffic (this step's logits out, the previous step's logits and the old score
+    // in, the new score out) happens in one dense phase at the end of the block.  Writes that trickle
+    // into a saturated read stream were measured to cost ~5% of the kernel per 1% of extra bytes.
     auto load_tile = [&](u32x4 (&kr)[U], u32x4 (&vr)[U], const char* kp, const char* vp, int base, int lead, int cnt) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {      // masked lanes re-read a valid row of the run
