@@ -195,28 +195,67 @@ __global__ __launch_bounds__(256) void obs_col_sums_kernel(const ObsArgs a, cons
 //
 // One template serves both steps.  A wave keeps 64 "stationary" vectors in registers as the B operand of
 // v_mfma_f32_16x16x32 (4 column tiles of 16) and streams tiles of 16 "moving" vectors through the A
-// operand; lane (j, q) = (lane % 16, lane / 16) loads, of vector j of a tile, the 16-byte chunks 4p + q
+// operand; lane (j, q) = (lane % 16, lane / 16) holds, of vector j of a tile, the 16-byte pieces 4p + q
 // (a permutation of the contraction index that both operands share), and receives the four products of
 // moving vectors 4q .. 4q+3 with stationary vector j.
 //   step 1 (row statistics): stationary = 64 queries of one head, moving = the keys they may see;
 //           every lane keeps a running (max, sum) of its query over its keys; merged over q at the end.
 //   step 2 (column sums):    stationary = 64 keys, moving = the queries that may see them, head after
 //           head of the group; every lane adds exp2(s - max_i) / sum_i of its key over its queries.
-// The four waves of a block take adjacent groups of 64 stationary vectors and stream the same tiles.
+// The four waves of a block take adjacent groups of 64 stationary vectors and share the moving rows: the
+// block copies them, kChunk rows at a time, into one of two LDS buffers while it computes on the other
+// (global loads of chunk c + 1 are issued before the tiles of chunk c and stored after them, one barrier
+// per chunk).  A wave reading its tiles straight from memory, one tile ahead, spent more than half its
+// time waiting for them.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes of packed 16-bit elements
 
-template <int DT> __device__ inline f32x4 mma16(const uint4& a, const uint4& b, f32x4 c);
-template <> __device__ inline f32x4 mma16<BUZZ_BF16>(const uint4& a, const uint4& b, f32x4 c) {
+template <int DT> __device__ inline f32x4 mma16(const u32x4& a, const u32x4& b, f32x4 c);
+template <> __device__ inline f32x4 mma16<BUZZ_BF16>(const u32x4& a, const u32x4& b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
-template <> __device__ inline f32x4 mma16<BUZZ_FP16>(const uint4& a, const uint4& b, f32x4 c) {
+template <> __device__ inline f32x4 mma16<BUZZ_FP16>(const u32x4& a, const u32x4& b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
 constexpr int kMmaCols = 64;            // stationary vectors per wave
 constexpr int kMmaBlockCols = 256;      // ... per block of four waves
+
+// The moving rows of one chunk in LDS.  A row occupies its D * 2 bytes plus 16: with that pitch the 16
+// lanes that read the same piece of 16 different rows fall on 16 different groups of four banks.
+template <int D>
+struct MovingChunk {
+    static constexpr int ROWB = D * 2, PIECES = ROWB / 16, PITCH = ROWB + 16;
+    static constexpr int ROWS = D == 256 ? 32 : 64;                   // two buffers stay within 64 KB of LDS
+    static constexpr int PER_THREAD = ROWS * PIECES / 256;            // 16-byte pieces a thread copies per chunk
+    static_assert(ROWS * PIECES % 256 == 0, "the block copies whole rounds of 256 pieces");
+    // issue the loads of rows row0 .. row0 + ROWS - 1 (clamped to last_row) of the array at `base`
+    static __device__ inline void request(u32x4 (&r)[PER_THREAD], const char* base, int row0, int last_row)
+    {
+#pragma unroll
+        for (int k = 0; k < PER_THREAD; ++k) {
+            const int piece = threadIdx.x + 256 * k, row = piece / PIECES, col = piece - row * PIECES;
+            r[k] = *(const u32x4*)(base + (size_t)min(row0 + row, last_row) * ROWB + col * 16);
+        }
+    }
+    static __device__ inline void store(char* buf, const u32x4 (&r)[PER_THREAD])
+    {
+#pragma unroll
+        for (int k = 0; k < PER_THREAD; ++k) {
+            const int piece = threadIdx.x + 256 * k, row = piece / PIECES, col = piece - row * PIECES;
+            *(u32x4*)(buf + row * PITCH + col * 16) = r[k];
+        }
+    }
+    // A operand of tile `tile` (16 rows) of the chunk for this lane
+    static __device__ inline void fetch(u32x4 (&f)[D / 32], const char* buf, int tile, int j, int q)
+    {
+        const char* row = buf + (16 * tile + j) * PITCH + q * 16;
+#pragma unroll
+        for (int p = 0; p < D / 32; ++p) f[p] = *(const u32x4*)(row + p * 64);
+    }
+};
 
 template <int DT, int D, int STEP, bool LOGN>
 __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
@@ -226,13 +265,19 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
     auto qscale = [&](int pos) {
         return LOGN ? a.scale_log2 * (logf((float)(pos + 1)) * (1.0f / 6.2383246250395077f)) : a.scale_log2;
     };
-    constexpr int ROWB = D * 2, QP = D / 32, CT = kMmaCols / 16;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    using MC = MovingChunk<D>;
+    constexpr int ROWB = D * 2, QP = D / 32, CT = kMmaCols / 16, CH = MC::ROWS;
+    constexpr bool AHEAD = D <= 128;                       // a second operand buffer fits the register budget
+    __shared__ __align__(16) char sm_rows[2][CH * MC::PITCH];
+    __shared__ float2 sm_stat[2][CH];                      // step 2: (max, 1 / sum) of the chunk's queries
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform values stay in scalar registers
     const int j = lane & 15, q = lane >> 4;
     const int G = a.Hq / a.Hkv;
     const int t_end = a.t_begin + a.t_count;               // queries [t_begin, t_end) of q_obs are scored by this pass
     const int shift = a.N - a.n_obs;                       // prompt position of query t is shift + t
-    auto chunk = [&](const char* row, int p) { return *(const uint4*)(row + (4 * p + q) * 16); };
+    auto piece = [&](const char* row, int p) { return *(const u32x4*)(row + (4 * p + q) * 16); };
+    u32x4 staged[MC::PER_THREAD];
 
     if constexpr (STEP == 1) {
         const int head = blockIdx.x;                       // b * Hq + h
@@ -240,11 +285,14 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
         const int unit = b * a.Hkv + h / G;
         // the latest queries see the most keys: their blocks go first, for all heads, so that the launch
         // ends with the short blocks (blockIdx.x, which the dispatcher advances first, is the head)
-        const int t_base = a.t_begin + ((int)gridDim.y - 1 - (int)blockIdx.y) * kMmaBlockCols + wave * kMmaCols;
-        if (t_base >= t_end) return;
+        const int t_block = a.t_begin + ((int)gridDim.y - 1 - (int)blockIdx.y) * kMmaBlockCols;
+        if (t_block >= t_end) return;
+        const int t_base = t_block + wave * kMmaCols;
+        const bool active = t_base < t_end;                // a wave without queries still copies and synchronises
         const char* Qb = (const char*)a.q_obs + (size_t)head * a.n_obs * ROWB;
         const char* Kb = (const char*)a.K + (size_t)unit * a.N * ROWB;
-        uint4 qf[CT][QP];
+        constexpr float kRefStart = -1.0e30f, kRefSlack = 1073741824.0f;   // 2^30
+        u32x4 qf[CT][QP];
         int pos[CT];
         float scale[CT], m[CT], l[CT];
 #pragma unroll
@@ -254,145 +302,183 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
             scale[ct] = qscale(max(pos[ct], 0));
             const char* row = Qb + (size_t)min(t, a.n_obs - 1) * ROWB;
 #pragma unroll
-            for (int p = 0; p < QP; ++p) qf[ct][p] = chunk(row, p);
-            m[ct] = -INFINITY; l[ct] = 0.f;
+            for (int p = 0; p < QP; ++p) qf[ct][p] = piece(row, p);
+            m[ct] = kRefStart; l[ct] = 0.f;
         }
         const int k_last = shift + min(t_base + kMmaCols, t_end) - 1;   // the wave's latest query sees keys 0 .. k_last
         const int k_free = shift + t_base;                 // keys up to here are visible to every query of the wave
-        auto load_keys = [&](uint4 (&kf)[QP], int k0) {
-            const char* row = Kb + (size_t)min(k0 + j, a.N - 1) * ROWB;
-#pragma unroll
-            for (int p = 0; p < QP; ++p) kf[p] = chunk(row, p);
-        };
-        // m[] holds the running maximum of the RAW products (the scale of a query is a positive constant, so
-        // the order is the same) and the scale enters through one fma per element: exp2(s * scale - m * scale)
-        auto consume_as = [&](const uint4 (&kf)[QP], int k0, auto masked_tag) {
+        const int k_last_block = shift + min(t_block + kMmaBlockCols, t_end) - 1;
+        const int n_chunks = k_last_block / CH + 1;
+        // Lazy reference: a lane sums exp2(s * scale - ref) against a reference that only moves when it has
+        // to.  A 16 x 16 tile whose sum (for any of its queries) exceeds kRefSlack is redone the classic way:
+        // the reference rises to the running maximum and the sum so far is rescaled.  Elsewhere a tile costs
+        // one fma, one exp2 and one add per element and none of the maximum bookkeeping.  The reference
+        // starts so low that the first tile with a visible key always takes the classic path; masked
+        // (-inf) products give exp2(-inf) = 0 against any finite reference.  m[] holds the reference in
+        // scaled (log2) units.
+        auto consume_as = [&](const u32x4 (&kf)[QP], int k0, auto masked_tag) {
             constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int p = 0; p < QP; ++p) acc = mma16<DT>(kf[p], qf[ct][p], acc);
-                float sv[4];
+                float sv[4], sum = 0.f;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {              // causal: key k0 + 4q + v against this lane's query
                     sv[v] = acc[v];
                     if (MASKED && k0 + 4 * q + v > pos[ct]) sv[v] = -INFINITY;
+                    sum += __builtin_amdgcn_exp2f(fmaf(sv[v], scale[ct], -m[ct]));
                 }
-                const float mn = fmaxf(fmaxf(m[ct], fmaxf(sv[0], sv[1])), fmaxf(sv[2], sv[3]));
-                const float mref = (MASKED && mn == -INFINITY) ? 0.f : mn;
-                const float off = -mref * scale[ct];
-                float sum = 0.f;
+                // wave-uniform and rare after the first tiles; !(<=) also catches a sum that overflowed
+                if (__builtin_amdgcn_ballot_w64(!(sum <= kRefSlack)) != 0) {
+                    const float top = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])) * scale[ct];
+                    const float ref = fmaxf(m[ct], top);   // unchanged where the tile brought nothing larger
+                    l[ct] *= __builtin_amdgcn_exp2f(m[ct] - ref);   // exactly 1 where the reference stands still
+                    m[ct] = ref;
+                    sum = 0.f;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f(fmaf(sv[v], scale[ct], off));
-                // (the rescale factor must be exactly 1 while the maximum stands still: an fma against the
-                // rounded offset would leave a residual of the same sign tile after tile)
-                l[ct] = fmaf(l[ct], __builtin_amdgcn_exp2f((m[ct] - mref) * scale[ct]), sum);
-                m[ct] = mn;
+                    for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f(fmaf(sv[v], scale[ct], -ref));
+                }
+                l[ct] += sum;
             }
         };
-        auto consume = [&](const uint4 (&kf)[QP], int k0) {
-            // wave-uniform: does a causal boundary or the end of the query list cross this tile?
-            if (k0 + 15 > k_free || t_base + kMmaCols > t_end) consume_as(kf, k0, std::true_type{});
-            else consume_as(kf, k0, std::false_type{});
-        };
-        uint4 ka[QP], kb[QP];                              // two tile buffers: the next tile is requested first
-        load_keys(ka, 0);
-        for (int k0 = 0; k0 <= k_last; k0 += 32) {
-            if (k0 + 16 <= k_last) load_keys(kb, k0 + 16);
-            consume(ka, k0);
-            if (k0 + 16 > k_last) break;
-            if (k0 + 32 <= k_last) load_keys(ka, k0 + 32);
-            consume(kb, k0 + 16);
+        MC::request(staged, Kb, 0, a.N - 1);
+        MC::store(sm_rows[0], staged);
+        __syncthreads();
+        for (int c = 0; c < n_chunks; ++c) {
+            const bool more = c + 1 < n_chunks;
+            if (more) MC::request(staged, Kb, (c + 1) * CH, a.N - 1);
+            if (active) {
+                // (head_dim <= 128) the operand of tile i + 1 leaves LDS while tile i is computed; reading
+                // past the wave's last tile stays inside the buffer and is never used
+                u32x4 kf[2][QP];
+                MC::fetch(kf[0], sm_rows[c & 1], 0, j, q);
+#pragma unroll
+                for (int tile = 0; tile < CH / 16; ++tile) {
+                    const int k0 = c * CH + 16 * tile;
+                    if (AHEAD && tile + 1 < CH / 16) MC::fetch(kf[(tile + 1) & 1], sm_rows[c & 1], tile + 1, j, q);
+                    if (!AHEAD && tile > 0) MC::fetch(kf[0], sm_rows[c & 1], tile, j, q);
+                    if (k0 <= k_last) {
+                        // wave-uniform: does a causal boundary or the end of the query list cross this tile?
+                        if (k0 + 15 > k_free || t_base + kMmaCols > t_end) consume_as(kf[AHEAD ? tile & 1 : 0], k0, std::true_type{});
+                        else consume_as(kf[AHEAD ? tile & 1 : 0], k0, std::false_type{});
+                    }
+                }
+            }
+            if (more) MC::store(sm_rows[(c + 1) & 1], staged);
+            __syncthreads();
         }
+        if (!active) return;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {                  // merge the four key subsets of a query
 #pragma unroll
             for (int off = 16; off < 64; off <<= 1) {
                 const float mo = __shfl_xor(m[ct], off), lo = __shfl_xor(l[ct], off);
-                const float mn = fmaxf(m[ct], mo);
-                const float mref = mn == -INFINITY ? 0.f : mn;
-                l[ct] = l[ct] * __builtin_amdgcn_exp2f((m[ct] - mref) * scale[ct]) +
-                        lo * __builtin_amdgcn_exp2f((mo - mref) * scale[ct]);
-                m[ct] = mn;
+                const float ref = fmaxf(m[ct], mo);       // finite: every lane's reference is
+                l[ct] = l[ct] * __builtin_amdgcn_exp2f(m[ct] - ref) + lo * __builtin_amdgcn_exp2f(mo - ref);
+                m[ct] = ref;
             }
             const int t = t_base + 16 * ct + j;
             if (q == 0 && t < t_end) {
                 float* st = a.stats + ((size_t)head * kObsPassRows + (t - a.t_begin)) * 2;
-                st[0] = m[ct] * scale[ct];                // maximum of the scaled logits
+                st[0] = m[ct];                             // reference of the scaled logits (at most their maximum)
                 st[1] = 1.0f / l[ct];                      // key 0 is visible to every query: l > 0
             }
         }
     } else {
         const int unit = blockIdx.x;                       // the earliest keys are seen by the most queries: they go first
         const int b = unit / a.Hkv, kvh = unit - b * a.Hkv;
-        const int j_base = blockIdx.y * kMmaBlockCols + wave * kMmaCols;
-        if (j_base >= a.N) return;
+        const int j_block = blockIdx.y * kMmaBlockCols;
+        const int j_base = j_block + wave * kMmaCols;
+        const bool active = j_base < a.N;
         const char* Kb = (const char*)a.K + (size_t)unit * a.N * ROWB;
-        uint4 kf[CT][QP];
+        u32x4 kf[CT][QP];
         float col[CT];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             const char* row = Kb + (size_t)min(j_base + 16 * ct + j, a.N - 1) * ROWB;
 #pragma unroll
-            for (int p = 0; p < QP; ++p) kf[ct][p] = chunk(row, p);
+            for (int p = 0; p < QP; ++p) kf[ct][p] = piece(row, p);
             col[ct] = 0.f;
         }
-        // the first query that sees key j_base, on the tile grid anchored at t_begin
-        const int t_first = max(j_base - shift, a.t_begin);
-        const int t_lo = a.t_begin + ((t_first - a.t_begin) & ~15);
-        for (int g = 0; g < G; ++g) {
-            const int head = b * a.Hq + kvh * G + g;
-            const char* Qb = (const char*)a.q_obs + (size_t)head * a.n_obs * ROWB;
-            const float* st = a.stats + (size_t)head * kObsPassRows * 2;
-            struct Moving { uint4 qf[QP]; float2 st[4]; };
-            auto load_queries = [&](Moving& mv, int t0) {
-                const char* row = Qb + (size_t)min(t0 + j, a.n_obs - 1) * ROWB;
+        // the block streams the queries from the first one that sees its first key, on the chunk grid
+        // anchored at t_begin, for every head of the group in turn: item i = (head i / n_chunks, chunk i % n_chunks)
+        const int t_first = max(j_block - shift, a.t_begin);
+        const int t_lo = a.t_begin + (t_first - a.t_begin) / CH * CH;
+        const int n_chunks = t_lo < t_end ? (t_end - t_lo + CH - 1) / CH : 0;
+        const int n_items = n_chunks * G;
+        const int head0 = b * a.Hq + kvh * G;
+        float2 staged_stat = make_float2(0.f, 0.f);
+        auto request = [&](int item) {
+            const int g = item / n_chunks, t0 = t_lo + (item - g * n_chunks) * CH;
+            MC::request(staged, (const char*)a.q_obs + (size_t)(head0 + g) * a.n_obs * ROWB, t0, a.n_obs - 1);
+            if (threadIdx.x < CH)
+                staged_stat = *(const float2*)(a.stats + ((size_t)(head0 + g) * kObsPassRows +
+                                                          (min(t0 + (int)threadIdx.x, t_end - 1) - a.t_begin)) * 2);
+        };
+        auto store = [&](int buf) {
+            MC::store(sm_rows[buf], staged);
+            if (threadIdx.x < CH) sm_stat[buf][threadIdx.x] = staged_stat;
+        };
+        auto consume_as = [&](const u32x4 (&qf)[QP], const float2 (&st)[4], int t0, auto masked_tag) {
+            constexpr bool MASKED = decltype(masked_tag)::value;
+            float sc[4];
+            int posq[4];
 #pragma unroll
-                for (int p = 0; p < QP; ++p) mv.qf[p] = chunk(row, p);
+            for (int v = 0; v < 4; ++v) {
+                const int t = t0 + 4 * q + v;
+                posq[v] = (!MASKED || t < t_end) ? shift + t : -1;
+                sc[v] = qscale(max(posq[v], 0));
+            }
 #pragma unroll
-                for (int v = 0; v < 4; ++v)                // statistics of moving queries 4q .. 4q+3
-                    mv.st[v] = *(const float2*)(st + (size_t)(min(t0 + 4 * q + v, t_end - 1) - a.t_begin) * 2);
-            };
-            auto consume_as = [&](const Moving& mv, int t0, auto masked_tag) {
-                constexpr bool MASKED = decltype(masked_tag)::value;
-                float sc[4];
-                int posq[4];
+            for (int ct = 0; ct < CT; ++ct) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int p = 0; p < QP; ++p) acc = mma16<DT>(qf[p], kf[ct][p], acc);
+                const int key = j_base + 16 * ct + j;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int t = t0 + 4 * q + v;
-                    posq[v] = (!MASKED || t < t_end) ? shift + t : -1;
-                    sc[v] = qscale(max(posq[v], 0));
+                    float e = __builtin_amdgcn_exp2f(fmaf(acc[v], sc[v], -st[v].x));
+                    if (MASKED && key > posq[v]) e = 0.f;
+                    col[ct] = fmaf(e, st[v].y, col[ct]);
                 }
+            }
+        };
+        if (n_items > 0) {
+            request(0);
+            store(0);
+        }
+        __syncthreads();
+        for (int item = 0; item < n_items; ++item) {
+            const bool more = item + 1 < n_items;
+            if (more) request(item + 1);
+            if (active) {
+                const int t_chunk = t_lo + (item % n_chunks) * CH;
+                // the operand of tile i + 1 leaves LDS while tile i is computed; the statistics are read with
+                // the tile itself, the products hide their latency
+                u32x4 qf[2][QP];
+                MC::fetch(qf[0], sm_rows[item & 1], 0, j, q);
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                for (int tile = 0; tile < CH / 16; ++tile) {
+                    const int t0 = t_chunk + 16 * tile;
+                    if (AHEAD && tile + 1 < CH / 16) MC::fetch(qf[(tile + 1) & 1], sm_rows[item & 1], tile + 1, j, q);
+                    if (!AHEAD && tile > 0) MC::fetch(qf[0], sm_rows[item & 1], tile, j, q);
+                    // skipped: tiles past the last query, and tiles none of whose queries sees any key of the wave
+                    if (t0 < t_end && shift + t0 + 15 >= j_base) {
+                        float2 st[4];
 #pragma unroll
-                    for (int p = 0; p < QP; ++p) acc = mma16<DT>(mv.qf[p], kf[ct][p], acc);
-                    const int key = j_base + 16 * ct + j;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        float e = __builtin_amdgcn_exp2f(fmaf(acc[v], sc[v], -mv.st[v].x));
-                        if (MASKED && key > posq[v]) e = 0.f;
-                        col[ct] = fmaf(e, mv.st[v].y, col[ct]);
+                        for (int v = 0; v < 4; ++v) st[v] = sm_stat[item & 1][16 * tile + 4 * q + v];
+                        // wave-uniform: unmasked if every query of the tile exists and sees every key of the wave
+                        if (t0 + 16 > t_end || shift + t0 < j_base + kMmaCols - 1) consume_as(qf[AHEAD ? tile & 1 : 0], st, t0, std::true_type{});
+                        else consume_as(qf[AHEAD ? tile & 1 : 0], st, t0, std::false_type{});
                     }
                 }
-            };
-            auto consume = [&](const Moving& mv, int t0) {
-                // wave-uniform: unmasked if every query of the tile exists and sees every key of the wave
-                if (t0 + 16 > t_end || shift + t0 < j_base + kMmaCols - 1) consume_as(mv, t0, std::true_type{});
-                else consume_as(mv, t0, std::false_type{});
-            };
-            Moving ma, mb;                                 // two tile buffers
-            if (t_lo < t_end) load_queries(ma, t_lo);
-            for (int t0 = t_lo; t0 < t_end; t0 += 32) {
-                if (t0 + 16 < t_end) load_queries(mb, t0 + 16);
-                consume(ma, t0);
-                if (t0 + 16 >= t_end) break;
-                if (t0 + 32 < t_end) load_queries(ma, t0 + 32);
-                consume(mb, t0 + 16);
             }
+            if (more) store((item + 1) & 1);
+            __syncthreads();
         }
+        if (!active) return;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             float c = col[ct] + __shfl_xor(col[ct], 16);
