@@ -116,6 +116,24 @@ def test_prefill_scores_from_every_prompt_query(dtype, G):
     run(wl, units=[(0, 1)])
 
 
+@pytest.mark.parametrize("G", [1, 2])
+def test_prefill_scores_when_logits_jump(G):
+    """Key rows of growing norm late in the prompt: the scaled logits of one query jump by ~20, then by far more
+    than 2^7 in log2 units, so a softmax sum taken against an earlier reference overflows single precision and
+    the matrix-core scoring has to move its reference (both when the sum grows large and when it is infinite)."""
+    wl = small(batch=1, n_kv_heads=2, n_q_heads=2 * G, head_dim=128, dtype="fp16", prompt=900, decode_steps=6,
+               sink=4, window=64, segment=16, keep=2, evict_every=8, n_obs=900)
+    p = prompt_inputs(wl, device="cuda")
+    d = decode_inputs(wl, device="cuda")
+    K = p["K"].float()
+    K[:, :, 300:304] *= 20.0
+    K[:, :, 520:523] *= 60.0
+    K[:, 1, 700:702] *= 200.0
+    p["K"] = K.to(p["K"].dtype)
+    st = lockstep().run_lockstep(wl, p, d)
+    print(f"[parity]   jumping logits G{G}: prefill-score {st['prefill_score']:.2e} out {st['out']:.2e}", flush=True)
+
+
 # ------------------------------------------------------------------ degenerate cases of the method
 def test_keep_zero_streaming():
     run(small(prompt=200, decode_steps=40, keep=0, n_obs=8))
