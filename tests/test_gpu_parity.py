@@ -116,6 +116,14 @@ def test_prefill_scores_from_every_prompt_query(dtype, G):
     run(wl, units=[(0, 1)])
 
 
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_prefill_scores_from_every_prompt_query_wide_rows(dtype):
+    """head_dim 256 takes the matrix-core scoring with 32-row chunks; several chunks, blocks and a ragged end."""
+    wl = small(batch=1, n_kv_heads=2, n_q_heads=4, head_dim=256, dtype=dtype, prompt=1130, decode_steps=4,
+               sink=4, window=200, segment=16, keep=2, evict_every=8, n_obs=1130)
+    run(wl, units=[(0, 1)])
+
+
 @pytest.mark.parametrize("G", [1, 2])
 def test_prefill_scores_when_logits_jump(G):
     """Key rows of growing norm late in the prompt: the scaled logits of one query jump by ~20, then by far more
