@@ -313,9 +313,8 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
         // to.  A 16 x 16 tile whose sum (for any of its queries) exceeds kRefSlack is redone the classic way:
         // the reference rises to the running maximum and the sum so far is rescaled.  Elsewhere a tile costs
         // one fma, one exp2 and one add per element and none of the maximum bookkeeping.  The reference
-        // starts so low that the first tile with a visible key always takes the classic path; masked
-        // (-inf) products give exp2(-inf) = 0 against any finite reference.  m[] holds the reference in
-        // scaled (log2) units.
+        // starts so low that the first tile with a visible key always takes the classic path.  m[] holds
+        // the reference in scaled (log2) units.
         auto consume_as = [&](const u32x4 (&kf)[QP], int k0, auto masked_tag) {
             constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
@@ -323,22 +322,30 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int p = 0; p < QP; ++p) acc = mma16<DT>(kf[p], qf[ct][p], acc);
-                float sv[4], sum = 0.f;
+                // causal: key k0 + 4q + v against this lane's query.  An invisible key contributes 0 through a
+                // select, not through a product of -inf: the log-n scale of the first prompt query is 0.
+                bool vis[4];
+                float sum = 0.f;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {              // causal: key k0 + 4q + v against this lane's query
-                    sv[v] = acc[v];
-                    if (MASKED && k0 + 4 * q + v > pos[ct]) sv[v] = -INFINITY;
-                    sum += __builtin_amdgcn_exp2f(fmaf(sv[v], scale[ct], -m[ct]));
+                for (int v = 0; v < 4; ++v) {
+                    vis[v] = !MASKED || k0 + 4 * q + v <= pos[ct];
+                    const float e = __builtin_amdgcn_exp2f(fmaf(acc[v], scale[ct], -m[ct]));
+                    sum += vis[v] ? e : 0.f;
                 }
                 // wave-uniform and rare after the first tiles; !(<=) also catches a sum that overflowed
                 if (__builtin_amdgcn_ballot_w64(!(sum <= kRefSlack)) != 0) {
-                    const float top = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])) * scale[ct];
+                    float top = kRefStart;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) top = fmaxf(top, vis[v] ? acc[v] * scale[ct] : kRefStart);
                     const float ref = fmaxf(m[ct], top);   // unchanged where the tile brought nothing larger
                     l[ct] *= __builtin_amdgcn_exp2f(m[ct] - ref);   // exactly 1 where the reference stands still
                     m[ct] = ref;
                     sum = 0.f;
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f(fmaf(sv[v], scale[ct], -ref));
+                    for (int v = 0; v < 4; ++v) {
+                        const float e = __builtin_amdgcn_exp2f(fmaf(acc[v], scale[ct], -ref));
+                        sum += vis[v] ? e : 0.f;
+                    }
                 }
                 l[ct] += sum;
             }

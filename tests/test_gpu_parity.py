@@ -219,6 +219,13 @@ def test_log_n_scaled_attention_tracks_context_length():
     run(small(prompt=480, decode_steps=64, n_obs=24), log_n=True)          # crosses n = 512
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_log_n_prompt_scores_from_the_first_query_on(dtype):
+    """Sec. 3.5 at n = 1: log_512(1) = 0, the first prompt query attends uniformly (to its one visible key)."""
+    run(small(batch=1, n_kv_heads=2, n_q_heads=4, head_dim=128, dtype=dtype, prompt=330, decode_steps=12,
+              sink=4, window=64, segment=16, keep=2, evict_every=8, n_obs=330), log_n=True)
+
+
 def test_log_n_with_grouped_queries():
     run(small(batch=1, n_kv_heads=2, n_q_heads=8, head_dim=128, dtype="bf16", prompt=600, decode_steps=40,
               sink=4, window=64, segment=16, keep=2, evict_every=16, n_obs=20), log_n=True)
