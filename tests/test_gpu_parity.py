@@ -226,6 +226,13 @@ def test_log_n_prompt_scores_from_the_first_query_on(dtype):
               sink=4, window=64, segment=16, keep=2, evict_every=8, n_obs=330), log_n=True)
 
 
+@pytest.mark.parametrize("G,dtype", [(1, "fp32"), (4, "bf16")])
+def test_log_n_from_an_empty_cache(G, dtype):
+    """Sec. 3.5 during decode at n = 1, 2, ...: the scale starts at 0 and grows with the tracked length."""
+    run(small(batch=1, n_kv_heads=2, n_q_heads=2 * G, head_dim=128, dtype=dtype, prompt=0, decode_steps=70,
+              sink=2, window=16, segment=4, keep=1, evict_every=4, n_obs=0), log_n=True)
+
+
 def test_log_n_with_grouped_queries():
     run(small(batch=1, n_kv_heads=2, n_q_heads=8, head_dim=128, dtype="bf16", prompt=600, decode_steps=40,
               sink=4, window=64, segment=16, keep=2, evict_every=16, n_obs=20), log_n=True)
