@@ -164,8 +164,14 @@ def test_empty_prompt():
     run(small(prompt=0, decode_steps=60, sink=2, window=16, segment=4, keep=1, evict_every=4, n_obs=0))
 
 
-def test_segment_longer_than_wave():
-    run(small(prompt=1500, decode_steps=10, sink=4, window=64, segment=200, keep=5, evict_every=300, n_obs=16))
+@pytest.mark.parametrize("keep", [5, 150])
+def test_segment_longer_than_wave(keep):
+    run(small(prompt=1500, decode_steps=10, sink=4, window=64, segment=200, keep=keep, evict_every=300, n_obs=16))
+
+
+def test_longest_supported_segment():
+    """segment = 4096 (the limit): two full segments and a ragged one at prefill, ties broken by index."""
+    run(small(prompt=9000, decode_steps=6, sink=4, window=64, segment=4096, keep=9, evict_every=5000, n_obs=16))
 
 
 def test_unbuffered_eviction_every_step():
