@@ -15,8 +15,8 @@ import numpy as np
 import torch
 
 from oracle.buzz_oracle import OracleCache, OracleConfig
-from paper_2410_23079_amd import (FLAG_AUTO_EVICT, FLAG_DETERMINISTIC, FLAG_INTERVAL_NEW, FLAG_LOG_N,
-                                 FLAG_THRESHOLD_TOTAL, BuzzCache, BuzzConfig)
+from paper_2410_23079_amd import (FLAG_AUTO_EVICT, FLAG_CACHED, FLAG_DETERMINISTIC, FLAG_INTERVAL_NEW, FLAG_LOG_N,
+                                 FLAG_STREAMING, FLAG_THRESHOLD_TOTAL, BuzzCache, BuzzConfig)
 from workloads import Workload
 
 OUT_TOL = 2e-3      # contract: max |o - o_ref| / max |o_ref| per (batch, head) vector
@@ -77,8 +77,9 @@ def gpu_prompt_scores(wl: Workload, prompt, n_obs: int, flags: int = 0):
 
 def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=None, splits=0,
                  check_auto=True, capacity=0, log_n=False, threshold_total=None, deterministic=True,
-                 interval_new=False):
-    """Returns a dict of the worst errors seen; raises AssertionError on any parity failure."""
+                 interval_new=False, kv_loads=None):
+    """Returns a dict of the worst errors seen; raises AssertionError on any parity failure.
+    kv_loads: None (the library decides), "streaming" or "cached" (forces the K/V load flavour)."""
     G, D = wl.group, wl.head_dim
     N = prompt["K"].shape[2]
     steps = decode["q"].shape[0] if steps is None else steps
@@ -92,7 +93,8 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
     if threshold_total is None:
         threshold_total = wl.threshold_total
     vflags = ((FLAG_LOG_N if log_n else 0) | (FLAG_THRESHOLD_TOTAL if threshold_total else 0)
-              | (FLAG_DETERMINISTIC if deterministic else 0) | (FLAG_INTERVAL_NEW if interval_new else 0))
+              | (FLAG_DETERMINISTIC if deterministic else 0) | (FLAG_INTERVAL_NEW if interval_new else 0)
+              | {None: 0, "streaming": FLAG_STREAMING, "cached": FLAG_CACHED}[kv_loads])
     okw = dict(log_n=log_n, threshold_total=threshold_total, interval_new=interval_new)
 
     # ---- prompt scores: library vs oracle, then shared

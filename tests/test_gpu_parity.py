@@ -84,6 +84,15 @@ def test_single_block_units_default_mode(dtype):
     run(wl, splits=1, deterministic=False)
 
 
+@pytest.mark.parametrize("kv_loads", ["streaming", "cached"])
+@pytest.mark.parametrize("G,dtype", [(1, "fp16"), (4, "bf16"), (2, "fp32")])
+def test_forced_kv_load_flavour(G, dtype, kv_loads):
+    """Both load flavours of every kernel family, whatever the working-set size would have chosen."""
+    wl = small(batch=1, n_kv_heads=3, n_q_heads=3 * G, head_dim=128, dtype=dtype, prompt=1300, decode_steps=24,
+               sink=4, window=128, segment=16, keep=2, evict_every=16, n_obs=12)
+    run(wl, kv_loads=kv_loads)
+
+
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 def test_widest_rows_and_groups(dtype):
     """head_dim 256 with 8 query heads per kv head: the largest per-block footprint the kernels support."""
