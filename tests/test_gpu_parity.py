@@ -109,9 +109,10 @@ def test_split_counts(splits):
 
 
 @pytest.mark.parametrize("deterministic", [True, False])
-def test_more_units_than_compute_units(deterministic):
+@pytest.mark.parametrize("G,dtype", [(1, "bf16"), (4, "fp16"), (2, "fp32")])
+def test_more_units_than_compute_units(deterministic, G, dtype):
     """360 units on 256 compute units: one 4-wave block per unit, several blocks per compute unit."""
-    wl = small(batch=45, n_kv_heads=8, n_q_heads=8, head_dim=64, dtype="bf16", prompt=300, decode_steps=40,
+    wl = small(batch=45, n_kv_heads=8, n_q_heads=8 * G, head_dim=64, dtype=dtype, prompt=300, decode_steps=40,
                sink=2, window=150, segment=8, keep=2, evict_every=8, n_obs=4)
     st = run(wl, units=[(0, 0), (17, 3), (31, 7), (44, 5), (44, 7)], deterministic=deterministic)
     assert st["evictions"] == 5
