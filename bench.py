@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run the library's plain copy kernel once on this many MiB (for rocprofv3 --pmc runs: "
                          "its known size gives the scale of the byte counters)")
+    ap.add_argument("--pipe-probe", action="store_true",
+                    help="instead of a workload: time the matrix / vector instruction mix of the prompt-scoring "
+                         "kernels alone and print how far the two pipes overlap")
     ap.add_argument("--prefill-obs", type=int, default=0,
                     help="also time the prefill of one layer with this many observed prompt queries (prefill scoring; "
                          "off the decode metric) and report it as `prefill_scoring`")
@@ -134,6 +137,28 @@ def cpu_baseline(wl, budget_s=20.0):
                       f"scaled by units and {wl.layers} layer(s)"}
 
 
+def pipe_probe(iters=20000, clock_ghz=2.4):
+    """Cycles (at the nominal clock) a SIMD needs per 16 x 64 tile of the prompt-scoring instruction mix: its 16
+    MFMAs alone, its 48 vector instructions alone, both; 1, 2 and 3 waves per SIMD (256, 512, 768 blocks)."""
+    import torch
+    from paper_2410_23079_amd import bench_pipes
+    torch.cuda.set_device(0)
+    out = torch.empty(768 * 256, dtype=torch.float32, device="cuda:0")
+    res = {}
+    for blocks in (256, 512, 768):
+        waves = blocks * 4 / 1024
+        for name, work in (("mfma", 1), ("vector", 2), ("both", 3)):
+            bench_pipes(work, blocks, 100, out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            bench_pipes(work, blocks, iters, out)
+            e1.record()
+            e1.synchronize()
+            res[f"{name}_cycles_per_tile_{int(waves)}_waves_per_simd"] = round(
+                e0.elapsed_time(e1) * 1e-3 * clock_ghz * 1e9 / (iters * waves), 1)
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -144,6 +169,9 @@ def main():
     from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_STREAMING
     from workloads import decode_inputs, get_workload
 
+    if args.pipe_probe:
+        print(json.dumps({"pipe_probe": pipe_probe()}), flush=True)
+        return
     wl = get_workload(args.workload)
     layers = args.layers or wl.layers
     warmup = args.warmup if args.warmup is not None else min(64, wl.decode_steps // 8)

@@ -217,6 +217,16 @@ int buzz_cache_profile_read(buzz_cache_t* cache, buzz_profile_t* out);
 int buzz_bench_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /*
+ * Benchmark aid: how far the matrix and vector pipes of a SIMD overlap.  Every wave of `blocks` blocks of four
+ * waves repeats, `iters` times, the instruction mix of one 16 x 64 tile of the matrix-core prompt scoring
+ * (Sec. 3.2's attention probabilities summed per key): `work` 1 = its 16 MFMAs (16x16x32, fp16) only,
+ * 2 = its 48 vector instructions (16 x fma, exp2, fma) only, 3 = both, the vector work on the MFMA results.
+ * `out`: device buffer of blocks * 256 floats (written, content meaningless).  The caller times the launch.
+ * Errors: BUZZ_EINVAL (work outside 1..3, blocks or iters < 1, blocks > 65535, NULL out), BUZZ_EHIP.
+ */
+int buzz_bench_pipes(int32_t work, int32_t blocks, int32_t iters, float* out, void* hip_stream);
+
+/*
  * The eviction threshold the Parameter Estimation theorem (Sec. 3.4) recommends for stride s and window w
  * under BUZZ_FLAG_THRESHOLD_TOTAL: T = w (s^2 + 1)/(s + 1) for odd s, w (s - 1) for even s, rounded to the
  * nearest integer and at least 1.  Returns 0 for s < 1 or w < 0.  Pure host arithmetic.
