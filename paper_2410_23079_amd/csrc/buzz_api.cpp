@@ -104,7 +104,7 @@ int make_layout(const buzz_config_t* c, Layout* L)
     L->pscore = take((size_t)units * c->max_context * 4);
     {   // prefill scoring statistics: what the vector path (fp32) or the matrix-core path (16-bit) needs
         const size_t vec = (size_t)units * ceil_div(c->max_context, kObsKeyBlock) * kObsRows * 2 * 4;
-        const size_t mma = (size_t)c->batch * c->n_q_heads * kObsPassRows * 2 * 4;
+        const size_t mma = (size_t)c->batch * c->n_q_heads * kObsKeySplits * kObsPassRows * 2 * 4;
         L->obs_stats = take(c->kv_dtype == BUZZ_FP32 ? vec : mma);
     }
     L->total = off;
@@ -404,6 +404,13 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
                 oa.Hq = cfg.n_q_heads; oa.Hkv = cfg.n_kv_heads;
                 oa.scale_log2 = c->scale * 1.4426950408889634f;
                 oa.log_n = (cfg.flags & BUZZ_FLAG_LOG_N) ? 1 : 0;
+                {   // few observed queries leave the row-statistics step with fewer blocks than compute units:
+                    // then up to kObsKeySplits blocks share a query group's keys (at least 512 keys each)
+                    const int64_t blocks = (int64_t)cfg.batch * cfg.n_q_heads * ceil_div(oa.t_count, 256);
+                    int64_t ks = ceil_div(3 * (int64_t)compute_units(), blocks);
+                    if (ks > N / 512) ks = N / 512;
+                    oa.key_splits = (int32_t)(ks < 1 ? 1 : (ks > kObsKeySplits ? kObsKeySplits : ks));
+                }
                 if (hipError_t e = launch_obs_scores(cfg.kv_dtype, cfg.head_dim, G, oa, L.units, st)) return hip_rc(e);
             }
         }

@@ -122,17 +122,20 @@ struct ObsArgs {               // prefill scoring: causal attention of observed 
     const void* q_obs;         // [B][Hq][n_obs][D]; query t sits at prompt position N - n_obs + t
     float* score;              // [units][N]   accumulated in place
     float* stats;              // vector path: [units][key_blocks][kObsRows][2] per key-block (max, sum) of every query
-                               // row; matrix-core path: [B * Hq][kObsPassRows][2] (max, 1/sum) of every query
+                               // row; matrix-core path: [B * Hq][key_splits][kObsPassRows][2] (reference, sum) of
+                               // every query over each part of its keys
     int32_t N, n_obs;
     int32_t t_begin, t_count;  // queries scored by this pass; at most obs_pass_queries()
     int32_t Hq, Hkv;
     int32_t log_n;             // 1: a query at prompt position i is scaled by log(i + 1) / log(512) (Sec. 3.5)
+    int32_t key_splits;        // matrix-core path: blocks that share the keys of one group of 256 queries (1..kObsKeySplits)
     float scale_log2;
 };
 
 constexpr int kObsRows = 256;        // query rows (query x group member) per pass = threads per block
 constexpr int kObsKeyBlock = 1024;   // keys per block of the row-statistics kernel
-constexpr int kObsPassRows = 4096;   // matrix-core scoring: queries per head and pass (stats: [heads][kObsPassRows][2])
+constexpr int kObsPassRows = 4096;   // matrix-core scoring: queries per head and pass
+constexpr int kObsKeySplits = 4;     // ... and the most blocks that share one query group's keys
 
 // Optional event pair: when both are non-null the launch records the kernel's own begin / end
 // timestamps into them (used by the benchmark profiling pass).

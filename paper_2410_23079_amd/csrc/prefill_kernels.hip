@@ -285,7 +285,10 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
         const int unit = b * a.Hkv + h / G;
         // the latest queries see the most keys: their blocks go first, for all heads, so that the launch
         // ends with the short blocks (blockIdx.x, which the dispatcher advances first, is the head)
-        const int t_block = a.t_begin + ((int)gridDim.y - 1 - (int)blockIdx.y) * kMmaBlockCols;
+        // blockIdx.y = (group of 256 queries, part of its keys): a.key_splits blocks share a group
+        const int q_blocks = (int)gridDim.y / a.key_splits;
+        const int part = (int)blockIdx.y % a.key_splits;
+        const int t_block = a.t_begin + (q_blocks - 1 - (int)blockIdx.y / a.key_splits) * kMmaBlockCols;
         if (t_block >= t_end) return;
         const int t_base = t_block + wave * kMmaCols;
         const bool active = t_base < t_end;                // a wave without queries still copies and synchronises
@@ -309,6 +312,8 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
         const int k_free = shift + t_base;                 // keys up to here are visible to every query of the wave
         const int k_last_block = shift + min(t_block + kMmaBlockCols, t_end) - 1;
         const int n_chunks = k_last_block / CH + 1;
+        const int per_part = (n_chunks + a.key_splits - 1) / a.key_splits;
+        const int c_begin = part * per_part, c_end = min(n_chunks, c_begin + per_part);   // this block's chunks
         // Lazy reference: a lane sums exp2(s * scale - ref) against a reference that only moves when it has
         // to.  A 16 x 16 tile whose sum (for any of its queries) exceeds kRefSlack is redone the classic way:
         // the reference rises to the running maximum and the sum so far is rescaled.  Elsewhere a tile costs
@@ -350,11 +355,11 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
                 l[ct] += sum;
             }
         };
-        MC::request(staged, Kb, 0, a.N - 1);
-        MC::store(sm_rows[0], staged);
+        MC::request(staged, Kb, c_begin * CH, a.N - 1);
+        MC::store(sm_rows[c_begin & 1], staged);
         __syncthreads();
-        for (int c = 0; c < n_chunks; ++c) {
-            const bool more = c + 1 < n_chunks;
+        for (int c = c_begin; c < c_end; ++c) {
+            const bool more = c + 1 < c_end;
             if (more) MC::request(staged, Kb, (c + 1) * CH, a.N - 1);
             if (active) {
                 // (head_dim <= 128) the operand of tile i + 1 leaves LDS while tile i is computed; reading
@@ -387,10 +392,10 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
                 m[ct] = ref;
             }
             const int t = t_base + 16 * ct + j;
-            if (q == 0 && t < t_end) {
-                float* st = a.stats + ((size_t)head * kObsPassRows + (t - a.t_begin)) * 2;
+            if (q == 0 && t < t_end) {                     // (a part without visible keys leaves (kRefStart, 0))
+                float* st = a.stats + (((size_t)head * a.key_splits + part) * kObsPassRows + (t - a.t_begin)) * 2;
                 st[0] = m[ct];                             // reference of the scaled logits (at most their maximum)
-                st[1] = 1.0f / l[ct];                      // key 0 is visible to every query: l > 0
+                st[1] = l[ct];
             }
         }
     } else {
@@ -420,9 +425,22 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
         auto request = [&](int item) {
             const int g = item / n_chunks, t0 = t_lo + (item - g * n_chunks) * CH;
             MC::request(staged, (const char*)a.q_obs + (size_t)(head0 + g) * a.n_obs * ROWB, t0, a.n_obs - 1);
-            if (threadIdx.x < CH)
-                staged_stat = *(const float2*)(a.stats + ((size_t)(head0 + g) * kObsPassRows +
-                                                          (min(t0 + (int)threadIdx.x, t_end - 1) - a.t_begin)) * 2);
+            if (threadIdx.x < CH) {                        // merge the parts: (reference, sum) -> (reference, 1 / sum)
+                const float* st = a.stats + ((size_t)(head0 + g) * a.key_splits * kObsPassRows +
+                                             (min(t0 + (int)threadIdx.x, t_end - 1) - a.t_begin)) * 2;
+                float2 part[kObsKeySplits];
+#pragma unroll
+                for (int k = 0; k < kObsKeySplits; ++k)
+                    part[k] = *(const float2*)(st + (size_t)min(k, a.key_splits - 1) * kObsPassRows * 2);
+                float ref = part[0].x;
+#pragma unroll
+                for (int k = 1; k < kObsKeySplits; ++k) ref = fmaxf(ref, part[k].x);   // part 0 holds key 0: finite, l > 0
+                float sum = 0.f;
+#pragma unroll
+                for (int k = 0; k < kObsKeySplits; ++k)
+                    if (k < a.key_splits) sum = fmaf(part[k].y, __builtin_amdgcn_exp2f(part[k].x - ref), sum);
+                staged_stat = make_float2(ref, 1.0f / sum);
+            }
         };
         auto store = [&](int buf) {
             MC::store(sm_rows[buf], staged);
@@ -537,7 +555,7 @@ template <int DT, int D>
 hipError_t launch_obs_mfma_t(const ObsArgs& a, int units, hipStream_t st, Timing tm)
 {
     const int heads = units / a.Hkv * a.Hq;
-    const dim3 g1(heads, (a.t_count + kMmaBlockCols - 1) / kMmaBlockCols), g2(units, (a.N + kMmaBlockCols - 1) / kMmaBlockCols);
+    const dim3 g1(heads, (a.t_count + kMmaBlockCols - 1) / kMmaBlockCols * a.key_splits), g2(units, (a.N + kMmaBlockCols - 1) / kMmaBlockCols);
     if (a.log_n) BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 1, true>), g1, dim3(256), 0, st, tm, a);
     else BUZZ_LAUNCH((obs_mfma_kernel<DT, D, 1, false>), g1, dim3(256), 0, st, tm, a);
     if (hipError_t e = hipGetLastError()) return e;
