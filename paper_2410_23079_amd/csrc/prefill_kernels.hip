@@ -231,13 +231,21 @@ struct MovingChunk {
     static constexpr int ROWS = D == 256 ? 32 : 64;                   // two buffers stay within 64 KB of LDS
     static constexpr int PER_THREAD = ROWS * PIECES / 256;            // 16-byte pieces a thread copies per chunk
     static_assert(ROWS * PIECES % 256 == 0, "the block copies whole rounds of 256 pieces");
-    // issue the loads of rows row0 .. row0 + ROWS - 1 (clamped to last_row) of the array at `base`
+    // issue the loads of rows row0 .. row0 + ROWS - 1 (clamped to last_row) of the array at `base`; rows are
+    // contiguous, so a chunk that lies inside the array is one block of memory and piece i sits 16 i bytes
+    // into it: a uniform base plus a per-thread constant, no address arithmetic per load
     static __device__ inline void request(u32x4 (&r)[PER_THREAD], const char* base, int row0, int last_row)
     {
+        if (row0 + ROWS - 1 <= last_row) {
+            const char* chunk = base + (size_t)row0 * ROWB;
 #pragma unroll
-        for (int k = 0; k < PER_THREAD; ++k) {
-            const int piece = threadIdx.x + 256 * k, row = piece / PIECES, col = piece - row * PIECES;
-            r[k] = *(const u32x4*)(base + (size_t)min(row0 + row, last_row) * ROWB + col * 16);
+            for (int k = 0; k < PER_THREAD; ++k) r[k] = *(const u32x4*)(chunk + (threadIdx.x + 256 * k) * 16);
+        } else {
+#pragma unroll
+            for (int k = 0; k < PER_THREAD; ++k) {
+                const int piece = threadIdx.x + 256 * k, row = piece / PIECES, col = piece - row * PIECES;
+                r[k] = *(const u32x4*)(base + (size_t)min(row0 + row, last_row) * ROWB + col * 16);
+            }
         }
     }
     static __device__ inline void store(char* buf, const u32x4 (&r)[PER_THREAD])
