@@ -297,10 +297,10 @@ __device__ inline void first_pass_scores(const AttnArgs& a, const SplitCtx& x, c
         if (a.pending && hi - lo > 0 && 4 * tid < cnt) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                p.sc[run].x += fast_exp2(p.lp[run][g].x - prev.M[g]) * prev.iL[g];
-                p.sc[run].y += fast_exp2(p.lp[run][g].y - prev.M[g]) * prev.iL[g];
-                p.sc[run].z += fast_exp2(p.lp[run][g].z - prev.M[g]) * prev.iL[g];
-                p.sc[run].w += fast_exp2(p.lp[run][g].w - prev.M[g]) * prev.iL[g];
+                p.sc[run].x = add_probability(p.sc[run].x, p.lp[run][g].x, prev.M[g], prev.iL[g]);
+                p.sc[run].y = add_probability(p.sc[run].y, p.lp[run][g].y, prev.M[g], prev.iL[g]);
+                p.sc[run].z = add_probability(p.sc[run].z, p.lp[run][g].z, prev.M[g], prev.iL[g]);
+                p.sc[run].w = add_probability(p.sc[run].w, p.lp[run][g].w, prev.M[g], prev.iL[g]);
             }
         }
     }
@@ -425,10 +425,10 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
                     for (int g = 0; g < G; ++g) lp[g] = *(const float4*)(logit_prev_u + (size_t)g * a.cap + ph);
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
-                        sc.x += fast_exp2(lp[g].x - Mp[g]) * iLp[g];
-                        sc.y += fast_exp2(lp[g].y - Mp[g]) * iLp[g];
-                        sc.z += fast_exp2(lp[g].z - Mp[g]) * iLp[g];
-                        sc.w += fast_exp2(lp[g].w - Mp[g]) * iLp[g];
+                        sc.x = add_probability(sc.x, lp[g].x, Mp[g], iLp[g]);
+                        sc.y = add_probability(sc.y, lp[g].y, Mp[g], iLp[g]);
+                        sc.z = add_probability(sc.z, lp[g].z, Mp[g], iLp[g]);
+                        sc.w = add_probability(sc.w, lp[g].w, Mp[g], iLp[g]);
                     }
                 }
             }
@@ -946,7 +946,7 @@ __global__ __launch_bounds__(256) void flush_scores_kernel(const AttnArgs a)
         const int ph = a.map.phys(j);
         float sc = a.score[ubase + ph];
 #pragma unroll
-        for (int g = 0; g < G; ++g) sc += fast_exp2(logit_u[(size_t)g * a.cap + ph] - M[g]) * iL[g];
+        for (int g = 0; g < G; ++g) sc = add_probability(sc, logit_u[(size_t)g * a.cap + ph], M[g], iL[g]);
         a.score[ubase + ph] = sc;
     }
 }

@@ -249,6 +249,31 @@ int evict_impl(buzz_cache_t* c, hipStream_t st)
     const int64_t take_last = newc % s < keep ? newc % s : keep;
     const int64_t new2 = keep * (newc / s) + take_last;        // every segment yields min(keep, len)
     if (old2 + new2 > L.old_cap) return BUZZ_ECAPACITY;
+    // Old rows that stay where they are (old stride 1) leave only the new rows to deal with, and one launch
+    // does that: a score update still pending stays pending for every row that keeps its place.
+    const bool in_place = old2 == c->n_old && (s + keep) * (int64_t)(4 * sizeof(float)) <= 65536;
+    if (in_place) {
+        if (!c->dry && new2 > 0) {
+            if (c->prof) c->prof_evictions += 1;
+            EvictArgs ea{};
+            ea.K = c->at<char>(L.K); ea.V = c->at<char>(L.V);
+            ea.score = c->at<float>(L.score); ea.pos = c->at<int32_t>(L.pos);
+            ea.logit_prev = c->pending ? c->at<float>(L.logit[c->last_buf]) : nullptr;
+            ea.stat_prev = c->at<float>(L.stat[c->last_buf]);
+            ea.map = c->map(); ea.lo = ea.map.front; ea.new_count = (int32_t)newc;
+            ea.segment = cfg.segment; ea.keep = L.keep;
+            ea.ignore_scores = (cfg.flags & BUZZ_FLAG_INTERVAL_NEW) ? 1 : 0;
+            ea.dst_start = (int32_t)(k + old2);
+            ea.cap = L.cap; ea.row_bytes = L.row_bytes; ea.G = L.G;
+            if (hipError_t e = launch_evict_new_rows(ea, L.units, st, prof_pair(c, 2))) return hip_rc(e);
+        } else if (!c->dry && c->prof) {
+            c->prof_evictions += 1;
+        }
+        c->n_old = old2 + new2;
+        c->head = (c->head + newc) % L.ring_cap;
+        c->tail -= newc;
+        return BUZZ_OK;
+    }
     if (int rc = flush_scores(c, st)) return rc;              // the selection reads the scores
     if (!c->dry) {
         if (c->prof) c->prof_evictions += 1;

@@ -91,6 +91,14 @@ struct AttnArgs {
     float scale_log2;    // softmax scale * log2(e)
 };
 
+// The lazy score update of one row and head: score + exp2(logit - max) / sum of the step that left it pending.
+// One definition for every kernel that applies it (the next decode step, the flush, the eviction), so that
+// whichever of them does, the bits are the same.
+__device__ inline float add_probability(float score, float logit, float row_max, float inv_sum)
+{
+    return fmaf(__builtin_amdgcn_exp2f(logit - row_max), inv_sum, score);
+}
+
 struct SelectArgs {
     const float* score;        // base of the score array the segments live in
     int64_t unit_stride;       // elements between units in `score`
@@ -101,6 +109,23 @@ struct SelectArgs {
     int32_t ignore_scores;     // ablation: keep the first `keep` rows of every segment (interval sampling)
     int32_t* sel;              // [units][sel_stride] logical source rows of the survivors, increasing
     int32_t sel_stride;
+};
+
+// Eviction of the new rows when the old rows stay where they are (old stride 1): segmented top-c and the
+// survivors' move in one launch.
+struct EvictArgs {
+    void* K; void* V;          // [units][cap][row_bytes]
+    float* score;              // [units][cap]
+    int32_t* pos;              // [units][cap]
+    float* logit_prev;         // [units][G][cap] logits of the last decode step, NULL when no score update is pending
+    const float* stat_prev;    // [units][G][2] its (max, 1 / sum)
+    RingMap map;               // logical -> physical rows before the eviction
+    int32_t lo;                // logical index of the first new row
+    int32_t new_count;         // rows to segment
+    int32_t segment, keep;
+    int32_t ignore_scores;     // ablation: keep the first `keep` rows of every segment
+    int32_t dst_start;         // physical (= logical) row the first survivor moves to
+    int32_t cap, row_bytes, G;
 };
 
 struct GatherArgs {
@@ -153,6 +178,7 @@ hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st, T
 hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st, Timing tm = {});
 hipError_t launch_fill_f32(float* dst, const float* src, int64_t n, hipStream_t st);  // src NULL => zeros
 hipError_t launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+hipError_t launch_evict_new_rows(const EvictArgs& a, int units, hipStream_t st, Timing tm = {});
 hipError_t launch_pipe_probe(int work, int blocks, int iters, float* out, hipStream_t st);
 hipError_t launch_obs_scores(int dtype, int D, int G, const ObsArgs& a, int units, hipStream_t st, Timing tm = {});
 int obs_pass_queries(int dtype, int G);   // queries of one head a single scoring pass covers

@@ -54,6 +54,81 @@ __global__ __launch_bounds__(256) void segment_topk_kernel(const SelectArgs a)
     }
 }
 
+// Eviction of the new rows in one launch, for caches whose old rows stay in place.  A wave ranks one segment
+// as above and then moves the segment's survivors itself (their destination depends on nothing but the
+// segment number and the rank).  A score update that the last decode step left pending is applied on the fly
+// to the rows of the segment -- nothing else needs it now: every other retained row keeps its physical place,
+// and the next decode step applies the update there as it would have without an eviction.  A survivor arrives
+// with its updated score, and its entry in that step's logit buffer is set to -inf so that the next step
+// adds exactly 0 for it.
+__global__ __launch_bounds__(256) void evict_new_rows_kernel(const EvictArgs a)
+{
+    extern __shared__ float lds[];                 // [kSelWaves][segment] scores, then [kSelWaves][keep] kept offsets
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seg = blockIdx.x * kSelWaves + wave, unit = blockIdx.y;
+    const int n_seg = (a.new_count + a.segment - 1) / a.segment;
+    if (seg >= n_seg) return;                      // no block-wide barrier below: a wave only reads what it wrote
+    const int start = seg * a.segment;
+    const int len = min(a.segment, a.new_count - start);
+    const int take = min(a.keep, len);
+    float* sc = lds + wave * a.segment;
+    int* kept = (int*)(lds + kSelWaves * a.segment) + wave * a.keep;
+    const size_t ubase = (size_t)unit * a.cap;
+    const float* logit_u = a.logit_prev ? a.logit_prev + ubase * a.G : nullptr;
+    auto current_score = [&](int ph) {             // the row's score with the pending update applied
+        float v = a.score[ubase + ph];
+        if (logit_u)
+            for (int g = 0; g < a.G; ++g)
+                v = add_probability(v, logit_u[(size_t)g * a.cap + ph], a.stat_prev[((size_t)unit * a.G + g) * 2],
+                                    a.stat_prev[((size_t)unit * a.G + g) * 2 + 1]);
+        return v;
+    };
+    for (int e = lane; e < len; e += 64) {
+        float v = a.ignore_scores ? 0.f : current_score(a.map.phys(a.lo + start + e));   // all equal: lowest indices win
+        if (v != v) v = -INFINITY;                 // NaN ranks below everything
+        sc[e] = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    int running = 0;
+    for (int e0 = 0; e0 < len; e0 += 64) {
+        const int e = e0 + lane;
+        bool kp = false;
+        if (e < len) {
+            const float v = sc[e];
+            int before = 0;                        // rows of the segment that rank strictly before row e
+            for (int i = 0; i < len; ++i) {
+                const float vi = sc[i];
+                before += (vi > v) || (vi == v && i < e);
+            }
+            kp = before < take;
+        }
+        const unsigned long long mask = __ballot(kp);
+        if (kp) kept[running + __popcll(mask & ((1ull << lane) - 1ull))] = e;
+        running += __popcll(mask);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // move the survivors: 16 bytes per lane, 64 / lpr rows per pass
+    const int lpr = a.row_bytes >> 4;              // lanes per row (at most 64)
+    const int c = lane % lpr, rr = lane / lpr, rows_per_pass = 64 / lpr;
+    for (int r = rr; r < take; r += rows_per_pass) {
+        const int sp = a.map.phys(a.lo + start + kept[r]);
+        const int dp = a.dst_start + seg * a.keep + r;
+        const size_t so = (ubase + sp) * a.row_bytes + c * 16, dof = (ubase + dp) * a.row_bytes + c * 16;
+        *(uint4*)((char*)a.K + dof) = *(const uint4*)((const char*)a.K + so);
+        *(uint4*)((char*)a.V + dof) = *(const uint4*)((const char*)a.V + so);
+        if (c == 0) {
+            a.score[ubase + dp] = current_score(sp);
+            a.pos[ubase + dp] = a.pos[ubase + sp];
+            if (a.logit_prev)
+                for (int g = 0; g < a.G; ++g) a.logit_prev[ubase * a.G + (size_t)g * a.cap + dp] = -INFINITY;
+        }
+    }
+}
+
 constexpr int kGatherRowsPerBlock = 64;
 
 __global__ __launch_bounds__(256) void gather_rows_kernel(const GatherArgs a)
@@ -101,6 +176,17 @@ hipError_t launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream
     size_t blocks = (n16 + 255) / 256;
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(plain_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint4*)dst, (const uint4*)src, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_evict_new_rows(const EvictArgs& a, int units, hipStream_t st, Timing tm)
+{
+    const int n_seg = (a.new_count + a.segment - 1) / a.segment;
+    if (n_seg <= 0 || a.keep <= 0) return hipSuccess;
+    if (a.row_bytes > 1024 || (a.row_bytes & 15) || 64 % (a.row_bytes >> 4)) return hipErrorInvalidValue;
+    const dim3 grid((n_seg + kSelWaves - 1) / kSelWaves, units);
+    const size_t lds = (size_t)kSelWaves * (a.segment + a.keep) * sizeof(float);
+    BUZZ_LAUNCH(evict_new_rows_kernel, grid, dim3(256), lds, st, tm, a);
     return hipGetLastError();
 }
 
