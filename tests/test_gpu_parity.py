@@ -358,6 +358,32 @@ def test_free_run_parts_only_at_near_ties(name, kw):
     assert res["agreed"] >= 1
 
 
+def test_default_and_deterministic_modes_agree_over_many_steps():
+    """Config 4's shape (eight blocks per unit merge through device memory in every launch), 10 240 steps with
+    evictions: a cache in the default mode and one in the deterministic mode stay within rounding of each other.
+    (A merge that ran ahead of a partial showed up about once in 10^5 launches before the publishing waves
+    waited for their own stores.)"""
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_DETERMINISTIC, BuzzCache
+    ls = lockstep()
+    wl = get_workload("gqa8b_layer")
+    p, d = prompt_inputs(wl, device="cuda"), decode_inputs(wl, device="cuda")
+    steps = wl.decode_steps
+    caches = [BuzzCache(ls.buzz_config(wl, flags=FLAG_AUTO_EVICT | f, max_context=wl.prompt + steps + 1))
+              for f in (0, FLAG_DETERMINISTIC)]
+    outs = [torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device="cuda") for _ in caches]
+    worst = torch.zeros((), device="cuda")
+    for _ in range(10240 // steps):
+        for c in caches:
+            c.prefill(p["K"], p["V"], q_obs=p["q_obs"])
+        for t in range(steps):
+            for c, o in zip(caches, outs):
+                c.decode_step(d["q"][t], d["k"][t], d["v"][t], o)
+            worst = torch.maximum(worst, (outs[0] - outs[1]).abs().amax() / outs[1].abs().amax())
+        assert caches[0].lengths() == caches[1].lengths()
+    print(f"[parity]   default vs deterministic over 10240 steps: worst relative difference {float(worst):.2e}", flush=True)
+    assert float(worst) < 1e-4
+
+
 # ------------------------------------------------------------------ full-size configs, sampled units
 def sampled_units(wl, count, seed):
     r = np.random.default_rng(seed)
