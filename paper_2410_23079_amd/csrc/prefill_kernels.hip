@@ -199,9 +199,9 @@ __global__ __launch_bounds__(256) void obs_col_sums_kernel(const ObsArgs a, cons
 // (a permutation of the contraction index that both operands share), and receives the four products of
 // moving vectors 4q .. 4q+3 with stationary vector j.
 //   step 1 (row statistics): stationary = 64 queries of one head, moving = the keys they may see;
-//           every lane keeps a running (max, sum) of its query over its keys; merged over q at the end.
+//           every lane keeps a (reference, sum) of its query over its keys; merged over q at the end.
 //   step 2 (column sums):    stationary = 64 keys, moving = the queries that may see them, head after
-//           head of the group; every lane adds exp2(s - max_i) / sum_i of its key over its queries.
+//           head of the group; every lane adds exp2(s - reference_i) / sum_i of its key over its queries.
 // The four waves of a block take adjacent groups of 64 stationary vectors and share the moving rows: the
 // block copies them, kChunk rows at a time, into one of two LDS buffers while it computes on the other
 // (global loads of chunk c + 1 are issued before the tiles of chunk c and stored after them, one barrier
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
     constexpr int ROWB = D * 2, QP = D / 32, CT = kMmaCols / 16, CH = MC::ROWS;
     constexpr bool AHEAD = D <= 128;                       // a second operand buffer fits the register budget
     __shared__ __align__(16) char sm_rows[2][CH * MC::PITCH];
-    __shared__ float2 sm_stat[2][CH];                      // step 2: (max, 1 / sum) of the chunk's queries
+    __shared__ float2 sm_stat[2][CH];                      // step 2: (reference, 1 / sum) of the chunk's queries
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform values stay in scalar registers
     const int j = lane & 15, q = lane >> 4;
