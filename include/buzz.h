@@ -79,7 +79,7 @@ enum {
 /* Symbols follow the paper's notation table (Sec. 3.3). */
 typedef struct buzz_config {
     int32_t batch;        /* sequences per call */
-    int32_t n_q_heads;    /* query heads; multiple of n_kv_heads */
+    int32_t n_q_heads;    /* query heads; 1 to 8 times n_kv_heads */
     int32_t n_kv_heads;   /* key/value heads; the score of a row is summed over its query group */
     int32_t head_dim;     /* d of eq. 3; 64, 128 or 256 */
     int32_t kv_dtype;     /* BUZZ_FP32 / BUZZ_FP16 / BUZZ_BF16 */

@@ -953,7 +953,7 @@ __global__ __launch_bounds__(256) void flush_scores_kernel(const AttnArgs a)
 
 template <int G, bool NT> constexpr int unroll_for()
 {
-    return G == 1 ? (NT ? BUZZ_U_G1 : BUZZ_U_G1_CACHED) : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
+    return G == 1 ? (NT ? BUZZ_U_G1 : BUZZ_U_G1_CACHED) : (G == 2 ? BUZZ_U_G2 : (G <= 4 ? BUZZ_U_G4 : BUZZ_U_G8));
 }
 
 template <typename T, int D, int G>
@@ -992,7 +992,11 @@ hipError_t launch_split_g(int G, const AttnArgs& a, int units, hipStream_t st, T
     switch (G) {
         case 1: return launch_split_t<T, D, 1>(a, units, st, tm);
         case 2: return launch_split_t<T, D, 2>(a, units, st, tm);
+        case 3: return launch_split_t<T, D, 3>(a, units, st, tm);
         case 4: return launch_split_t<T, D, 4>(a, units, st, tm);
+        case 5: return launch_split_t<T, D, 5>(a, units, st, tm);
+        case 6: return launch_split_t<T, D, 6>(a, units, st, tm);
+        case 7: return launch_split_t<T, D, 7>(a, units, st, tm);
         case 8: return launch_split_t<T, D, 8>(a, units, st, tm);
     }
     return hipErrorInvalidValue;
@@ -1039,7 +1043,7 @@ bool attn_supported(int dtype, int D, int G)
 {
     if (dtype != BUZZ_FP32 && dtype != BUZZ_FP16 && dtype != BUZZ_BF16) return false;
     if (D != 64 && D != 128 && D != 256) return false;
-    return G == 1 || G == 2 || G == 4 || G == 8;
+    return G >= 1 && G <= 8;
 }
 
 int attn_tile_rows(int dtype, int D, int G)
@@ -1047,7 +1051,7 @@ int attn_tile_rows(int dtype, int D, int G)
     const int vec = dtype == BUZZ_FP32 ? 4 : 8;
     const int rpw = 64 / (D / vec);
     if (G >= 2 && dtype != BUZZ_FP32) return 16;          // matrix-core kernel: 16-row tiles
-    int u = G == 1 ? BUZZ_U_G1_CACHED : (G == 2 ? BUZZ_U_G2 : (G == 4 ? BUZZ_U_G4 : BUZZ_U_G8));
+    int u = G == 1 ? BUZZ_U_G1_CACHED : (G == 2 ? BUZZ_U_G2 : (G <= 4 ? BUZZ_U_G4 : BUZZ_U_G8));
     if (u * rpw < 4) u = 4 / rpw;
     return rpw * u;                                       // rows of one wave-wide trip
 }
@@ -1069,7 +1073,11 @@ hipError_t launch_flush_scores(int G, const AttnArgs& a, int units, hipStream_t 
     switch (G) {
         case 1: BUZZ_LAUNCH((flush_scores_kernel<1>), grid, block, 0, st, tm, a); break;
         case 2: BUZZ_LAUNCH((flush_scores_kernel<2>), grid, block, 0, st, tm, a); break;
+        case 3: BUZZ_LAUNCH((flush_scores_kernel<3>), grid, block, 0, st, tm, a); break;
         case 4: BUZZ_LAUNCH((flush_scores_kernel<4>), grid, block, 0, st, tm, a); break;
+        case 5: BUZZ_LAUNCH((flush_scores_kernel<5>), grid, block, 0, st, tm, a); break;
+        case 6: BUZZ_LAUNCH((flush_scores_kernel<6>), grid, block, 0, st, tm, a); break;
+        case 7: BUZZ_LAUNCH((flush_scores_kernel<7>), grid, block, 0, st, tm, a); break;
         case 8: BUZZ_LAUNCH((flush_scores_kernel<8>), grid, block, 0, st, tm, a); break;
         default: return hipErrorInvalidValue;
     }

@@ -29,7 +29,9 @@ constexpr int kMinSplitRows = 128;     // automatic split policy: no split short
 constexpr int kStageFloats = 4096;     // LDS logit staging of one split that every shape can have
 constexpr int kStageFloatsMax = 8192;  // ... and what a shape gets when the block's other LDS arrays leave room
 
-constexpr int kWideBlockMaxGD = 2048;  // 8-wave decode blocks only below this group size * head_dim (LDS)
+// 8-wave decode blocks only below this group size * head_dim: eight waves' partial outputs (32 bytes per
+// element) and kStageFloats of logit staging must fit 64 KB of LDS
+constexpr int kWideBlockMaxGD = 1505;
 
 // Floats of LDS staging (rows_per_split * group size) a decode block may use: as much as keeps the block's
 // LDS (the waves' partial outputs [waves][G][D] and running statistics, the staging) within 64 KB, between

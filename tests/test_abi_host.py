@@ -54,7 +54,7 @@ def test_invalid_configurations_are_rejected(bad):
     assert load_library().buzz_workspace_bytes(ctypes.byref(raw), ctypes.byref(out)) == -1
 
 
-@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(n_q_heads=6), dict(segment=5000)])
+@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(n_q_heads=18), dict(segment=5000)])
 def test_unsupported_shapes_say_so(bad):
     with pytest.raises(BuzzError) as e:
         workspace_bytes(cfg(**bad))

@@ -61,7 +61,7 @@ def test_tiny_paper_old_stride_with_capacity():
 # ------------------------------------------------------------------ shapes, dtypes, group sizes, ragged everything
 @pytest.mark.parametrize("dtype", ["fp32", "fp16", "bf16"])
 @pytest.mark.parametrize("D", [64, 128, 256])
-@pytest.mark.parametrize("G", [1, 2, 4, 8])
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_shapes(dtype, D, G):
     wl = small(batch=2, n_kv_heads=2, n_q_heads=2 * G, head_dim=D, dtype=dtype, prompt=300, decode_steps=45,
                sink=3, window=40, segment=7, keep=2, evict_every=10, n_obs=9)
