@@ -10,8 +10,9 @@
 //  - The scaled logit of every row is written to a scratch array.  A row's probability needs the
 //    maximum and sum over ALL splits, which only exist once the step is over, so the score update of
 //    step t is applied by step t+1 while it streams the same rows anyway (one lane per row, coalesced):
-//    score += sum_g exp2(logit_t - M_t[g]) / L_t[g].  flush_scores applies a pending update right away;
-//    the host calls it before anything reads the scores (eviction, export).
+//    score += sum_g exp2(logit_t - M_t[g]) / L_t[g].  flush_scores applies a pending update to every row
+//    right away (before an export, or an eviction that moves old rows); the usual eviction applies it only to
+//    the rows it ranks and leaves the rest pending.
 //  - The block that finishes last for a unit (atomic ticket, nobody waits) merges the split partials
 //    into the attention output and publishes (M, 1/L) for the next step's score update.
 #include <type_traits>
