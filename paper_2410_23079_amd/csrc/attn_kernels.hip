@@ -76,7 +76,7 @@ template <typename T> struct Elem;
 // cvt: 16 bytes -> VEC floats.  dot: sum over the 16 bytes of q * k in fp32 (16-bit types use the
 // two-element dot instruction on the raw words: exact products, fp32 accumulation, no conversion).
 template <> struct Elem<float> {
-    static constexpr int VEC = 4;
+    [[maybe_unused]] static constexpr int VEC = 4;
     static __device__ inline void cvt(const u32x4& r, float* f) {
         f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
         f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
@@ -89,7 +89,7 @@ template <> struct Elem<float> {
     }
 };
 template <> struct Elem<bf16_t> {
-    static constexpr int VEC = 8;
+    [[maybe_unused]] static constexpr int VEC = 8;
     static __device__ inline void cvt(const u32x4& r, float* f) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -107,7 +107,7 @@ template <> struct Elem<bf16_t> {
     }
 };
 template <> struct Elem<fp16_t> {
-    static constexpr int VEC = 8;
+    [[maybe_unused]] static constexpr int VEC = 8;
     static __device__ inline void cvt(const u32x4& r, float* f) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
