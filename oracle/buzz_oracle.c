@@ -35,9 +35,10 @@
  *     and emits them in index order;
  *   - interval sampling of old tokens keeps offsets 0, s^, 2 s^, ... ;
  *     s^ = floor((s+1)/2) unless the caller overrides it (s^ = 1 keeps all);
- *   - in prefill the eviction runs once when the new count is >= T and, for
- *     s^ > 1, again while sink + old + window + T exceeds the capacity
- *     (Remark 2);
+ *   - in prefill the eviction runs once when the count compared with T is
+ *     >= T, and again while the rows do not fit their container (Remark 2):
+ *     T + k + w rows when T bounds old + new tokens together, or an explicit
+ *     capacity less the T rows buffered before the next eviction;
  *   - optional variants: log-n scaled attention (Sec. 3.5) multiplies the
  *     softmax scale by log(n)/log(512), n = number of tokens the query sees,
  *     itself included; and the threshold may instead bound old + new tokens
@@ -299,15 +300,19 @@ int oracle_prefill(oracle_t *o, const double *K, const double *V, int64_t N,
                 rc = r;
             }
         }
-        if (old_stride_of(c) > 1 && c->capacity > 0) {
-            while (c->sink + x->n_old + c->window + c->evict_every > c->capacity) {
-                const int64_t before = x->n_old;
-                int r = unit_evict(c, x);
-                if (r || x->n_old >= before) {
+        /* Remark 2: keep sampling until the selected tokens fit their container.  Without an explicit
+         * capacity the container has T + k + w rows when T bounds old + new tokens together (the
+         * remark's own figure); when T counts new tokens only, one sampling is all there is.  An
+         * explicit capacity must also leave room for the T tokens buffered before the next eviction. */
+        const int64_t container = c->capacity > 0 ? c->capacity - c->evict_every
+                                  : (c->variant & 2) ? c->evict_every + c->sink + c->window : 0;
+        while (container > 0 && x->n > container && x->n > c->sink + c->window) {
+            const int64_t before = x->n;
+            int r = unit_evict(c, x);
+            if (r || x->n >= before) {             /* nothing left to thin (s^ = 1): it cannot fit */
 #pragma omp critical
-                    rc = r ? r : ORACLE_ECAPACITY;
-                    break;
-                }
+                rc = r ? r : ORACLE_ECAPACITY;
+                break;
             }
         }
     }

@@ -202,12 +202,10 @@ def test_total_threshold_sizes_match_oracle(seed):
     s, keep = int(r.integers(2, 9)), int(r.integers(1, 3))
     T = int(r.integers(20, 120))
     N, steps = int(r.integers(0, 600)), 300
-    sh = (s + 1) // 2
-    cap = k + w + 2 * T
     g = BuzzCache(cfg(sink=k, window=w, segment=s, keep=keep, evict_every=T, old_stride=0, max_context=N + steps,
                       flags=DRY | FLAG_THRESHOLD_TOTAL))
     o = OracleCache(OracleConfig(1, 1, 1, 2, sink=k, window=w, segment=s, keep=keep, evict_every=T, old_stride=0,
-                                 threshold_total=True, capacity=cap))
+                                 threshold_total=True))
     g.prefill(None, None, n_prompt=N)
     o.prefill(np.zeros((1, 1, N, 2)), np.zeros((1, 1, N, 2)))
     assert g.lengths() == o.lengths()

@@ -496,3 +496,121 @@ def test_interval_sampling_of_new_tokens_ignores_scores():
     o2.prefill(K, V, init_score=r.standard_normal((1, 1, N)))
     expect2 = np.concatenate([np.arange(k), np.sort(np.concatenate([mid[::s], mid[1::s]])), np.arange(N - w, N)])
     np.testing.assert_array_equal(o2.export()[3][0, 0], expect2)
+
+
+# ---------------------------------------------------------------- Remark 2: a prefill samples until the rows fit their container
+def replay_prefill(N, k, w, s, sh, T, c, score, capacity=0, total=False):
+    """Alg. 1's sampling applied to a prompt with Python slices and `sorted`, repeated as Remark 2 says.
+    Returns the retained token indices.  (Under either reading of T the count compared with T at a prefill
+    is the number of prompt tokens between sink and window: there are no old tokens yet.)"""
+    idx = list(range(N))
+    if N - k - w < T:                                    # fewer than T tokens between sink and window: keep all
+        return idx
+    mid = idx[k:N - w]
+    old = []
+    for a in range(0, len(mid), s):                      # Alg. 2 on the new tokens
+        seg = mid[a:a + s]
+        old += sorted(sorted(seg, key=lambda j: (-score[j], j))[:c])
+    if capacity:
+        fits = lambda rows: k + rows + w + T <= capacity     # room for the next T buffered tokens remains
+    elif total:
+        fits = lambda rows: k + rows + w <= T + k + w        # the remark's container of length T + k + w
+    else:
+        fits = lambda rows: True
+    while not fits(len(old)):
+        assert len(old[::sh]) < len(old), "cannot fit"
+        old = old[::sh]                                  # interval sampling of what are now old tokens
+    return idx[:k] + old + idx[N - w:]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_prefill_samples_until_it_fits_the_container(seed):
+    r = rng(400 + seed)
+    k, w = int(r.integers(0, 5)), int(r.integers(0, 12))
+    s, c = int(r.integers(2, 9)), int(r.integers(1, 3))
+    sh = int(r.choice([0, 2, 3, 4]))
+    eff = sh or (s + 1) // 2
+    if eff < 2:
+        sh = eff = 2
+    T = int(r.integers(4, 30))
+    N = int(r.integers(k + w + T, 700))
+    total = bool(seed % 2)
+    capacity = 0 if seed % 3 == 0 else k + w + T + int(r.integers(1, 12))
+    D = 2
+    K = np.zeros((1, 1, N, D))
+    K[0, 0, :, 0] = np.arange(N)
+    init = r.integers(0, 5, size=(1, 1, N)).astype(np.float64)       # ties everywhere
+    o = OracleCache(OracleConfig(1, 1, 1, D, sink=k, window=w, segment=s, keep=c, evict_every=T, old_stride=sh,
+                                 capacity=capacity, threshold_total=total))
+    o.prefill(K, -K, init_score=init)
+    expect = replay_prefill(N, k, w, s, eff, T, c, init[0, 0], capacity, total)
+    Ko, Vo, A, pos = o.export()
+    assert list(pos[0, 0]) == expect
+    assert o.lengths() == (len(expect), len(expect) - k - w, 0)
+    np.testing.assert_array_equal(Ko[0, 0, :, 0], expect)
+    np.testing.assert_array_equal(A[0, 0], init[0, 0, expect])
+    if capacity:
+        assert len(expect) + T <= capacity
+    elif total:
+        assert len(expect) <= T + k + w
+
+
+def test_prefill_container_literal_cases():
+    """N = 100, k = 2, w = 8, s = 5, s^ = 3, T = 10, all scores 0 (ties go to the lowest index): Alg. 2 keeps
+    tokens 2, 7, ..., 87 (18 of them).  Remark 2's container of T + k + w = 20 rows has room for 10, so one more
+    interval sampling leaves tokens 2, 17, ..., 77 (6).  A capacity of 25 rows leaves, after the T rows kept free
+    for buffering, room for 5: two more samplings, tokens 2 and 47.  Counting new tokens only and no capacity:
+    one sampling, 18 rows."""
+    N, k, w, s, T, D = 100, 2, 8, 5, 10, 1
+    z = np.zeros((1, 1, N, D))
+    window = list(range(92, 100))
+
+    def retained(**kw):
+        o = OracleCache(OracleConfig(1, 1, 1, D, sink=k, window=w, segment=s, keep=1, evict_every=T, old_stride=0, **kw))
+        o.prefill(z, z)
+        return list(o.export()[3][0, 0]), o.lengths()
+
+    pos, lens = retained(threshold_total=True)
+    assert pos == [0, 1, 2, 17, 32, 47, 62, 77] + window and lens == (16, 6, 0)
+    pos, lens = retained(capacity=25)
+    assert pos == [0, 1, 2, 47] + window and lens == (12, 2, 0)
+    pos, lens = retained(capacity=25, threshold_total=True)
+    assert pos == [0, 1, 2, 47] + window and lens == (12, 2, 0)
+    pos, lens = retained()
+    assert pos == [0, 1] + list(range(2, 92, 5)) + window and lens == (28, 18, 0)
+
+
+def test_prefill_that_cannot_fit_says_so():
+    """Survivors that persist (s^ = 1) cannot be thinned: a container they do not fit is an error, not a loop."""
+    from oracle.buzz_oracle import OracleError
+    z = np.zeros((1, 1, 100, 1))
+    o = OracleCache(OracleConfig(1, 1, 1, 1, sink=2, window=8, segment=5, keep=1, evict_every=10, old_stride=1,
+                                 capacity=25))
+    with pytest.raises(OracleError):
+        o.prefill(z, z)
+
+
+# ---------------------------------------------------------------- Alg. 1's first loops: when a prompt is sampled at all
+@pytest.mark.parametrize("total", [False, True])
+def test_prefill_trigger_boundary_literals(total):
+    """k = 2, w = 3, s = 4, keep 1, T = 8.  With T - 1 = 7 tokens between sink and window nothing is sampled
+    (12 rows stay); with exactly T = 8 the threshold is reached: two segments, 2 survivors, 7 rows; with 9 a
+    ragged third segment adds one: 8 rows."""
+    k, w, s, T, D = 2, 3, 4, 8, 1
+    for M, expect in ((7, (12, 0, 7)), (8, (7, 2, 0)), (9, (8, 3, 0))):
+        N = k + M + w
+        z = np.zeros((1, 1, N, D))
+        o = OracleCache(OracleConfig(1, 1, 1, D, sink=k, window=w, segment=s, keep=1, evict_every=T, old_stride=1,
+                                     threshold_total=total))
+        o.prefill(z, z)
+        assert o.lengths() == expect, (M, o.lengths())
+    # the same boundary during decoding: the eviction falls on the step that buffers the T-th token, not the next
+    o = OracleCache(OracleConfig(1, 1, 1, D, sink=k, window=w, segment=s, keep=1, evict_every=T, old_stride=1,
+                                 threshold_total=total))
+    o.prefill(np.zeros((1, 1, k + w, D)), np.zeros((1, 1, k + w, D)))
+    z = np.zeros((1, 1, D))
+    sizes = []
+    for _ in range(9):
+        o.decode_step(z, z, z)
+        sizes.append(o.lengths())
+    assert sizes[6] == (12, 0, 7) and sizes[7] == (7, 2, 0) and sizes[8] == (8, 2, 1)
