@@ -146,7 +146,10 @@ int buzz_prefill(buzz_cache_t* cache, const void* k, const void* v, int64_t n_pr
  *   k_new  [batch][n_kv_heads][head_dim], kv_dtype       v_new likewise
  *   out    [batch][n_q_heads][head_dim], fp32
  * Errors: BUZZ_EINVAL, BUZZ_ESTATE (no prefill yet), BUZZ_ECAPACITY (max_context
- *         reached, or window + buffer full because eviction was not called), BUZZ_EHIP.
+ *         reached; window + buffer full because eviction was not called; or, with
+ *         BUZZ_FLAG_AUTO_EVICT, the eviction this step would end with leaves more
+ *         survivors than an explicit `capacity` has room for -- checked before the
+ *         step is enqueued, so the token is not appended), BUZZ_EHIP.
  */
 int buzz_decode_step(buzz_cache_t* cache, const void* q, const void* k_new, const void* v_new,
                      float* out, void* hip_stream);

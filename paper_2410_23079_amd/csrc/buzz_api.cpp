@@ -219,6 +219,21 @@ GatherArgs cache_gather_base(const buzz_cache_t* c)
     return g;
 }
 
+// Sizes an eviction (the eviction branch of Alg. 1) would leave behind on a cache of n rows, n_old of them old:
+// old2 interval-sampled old rows, new2 segment survivors out of newc new rows.  False when nothing would be
+// evicted (Remark 1: no more than sink + window rows).
+struct EvictSizes { int64_t newc, old2, new2; };
+bool evict_sizes(const buzz_cache_t* c, int64_t n, int64_t n_old, EvictSizes* z)
+{
+    const int64_t k = c->cfg.sink, w = c->cfg.window, s = c->cfg.segment, keep = c->L.keep;
+    if (n <= k + w) return false;
+    const int64_t newc = n - k - n_old - w > 0 ? n - k - n_old - w : 0;
+    z->newc = newc;
+    z->old2 = ceil_div(n_old, c->L.old_stride);                // interval sampling keeps offsets 0, s^, 2 s^, ...
+    z->new2 = keep * (newc / s) + (newc % s < keep ? newc % s : keep);   // every segment yields min(keep, len)
+    return true;
+}
+
 // Applies the score update the last decode step left pending, so that the scores are current.
 int flush_scores(buzz_cache_t* c, hipStream_t st)
 {
@@ -241,13 +256,10 @@ int evict_impl(buzz_cache_t* c, hipStream_t st)
 {
     const buzz_config_t& cfg = c->cfg;
     const Layout& L = c->L;
-    const int64_t k = cfg.sink, w = cfg.window, s = cfg.segment, keep = L.keep;
-    if (c->n() <= k + w) return BUZZ_OK;                       // Remark 1
-    const int64_t newc = c->new_count();
-    const int64_t sh = L.old_stride;
-    const int64_t old2 = ceil_div(c->n_old, sh);               // interval sampling keeps offsets 0, s^, 2 s^, ...
-    const int64_t take_last = newc % s < keep ? newc % s : keep;
-    const int64_t new2 = keep * (newc / s) + take_last;        // every segment yields min(keep, len)
+    const int64_t k = cfg.sink, s = cfg.segment, keep = L.keep;
+    EvictSizes z;
+    if (!evict_sizes(c, c->n(), c->n_old, &z)) return BUZZ_OK; // Remark 1
+    const int64_t newc = z.newc, sh = L.old_stride, old2 = z.old2, new2 = z.new2;
     if (old2 + new2 > L.old_cap) return BUZZ_ECAPACITY;
     // Old rows that stay where they are (old stride 1) leave only the new rows to deal with, and one launch
     // does that: a score update still pending stays pending for every row that keeps its place.
@@ -502,6 +514,17 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
     const int64_t sink_filled = c->sink_filled + (to_sink ? 1 : 0);
     const int64_t tail = c->tail + (to_sink ? 0 : 1);
     const int64_t n = sink_filled + c->n_old + tail;
+    // With automatic eviction the step ends with one when the threshold is reached: whether its survivors fit
+    // is known now, before anything is enqueued or changed.
+    bool evict_after = false;
+    if (cfg.flags & BUZZ_FLAG_AUTO_EVICT) {
+        EvictSizes z;
+        if (evict_sizes(c, n, c->n_old, &z)) {
+            const int64_t count = (cfg.flags & BUZZ_FLAG_THRESHOLD_TOTAL) ? c->n_old + z.newc : z.newc;
+            evict_after = count >= cfg.evict_every;
+            if (evict_after && z.old2 + z.new2 > L.old_cap) return BUZZ_ECAPACITY;
+        }
+    }
 
     if (!c->dry) {
         AttnArgs a{};
@@ -557,7 +580,8 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
     c->sink_filled = sink_filled;
     c->tail = tail;
     c->tokens_seen += 1;
-    if ((cfg.flags & BUZZ_FLAG_AUTO_EVICT) && c->trigger_count() >= cfg.evict_every) return evict_impl(c, st);
+    if (evict_after || ((cfg.flags & BUZZ_FLAG_AUTO_EVICT) && c->trigger_count() >= cfg.evict_every))
+        return evict_impl(c, st);                              // cannot fail for capacity: checked above
     return BUZZ_OK;
 }
 

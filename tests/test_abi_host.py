@@ -215,3 +215,24 @@ def test_total_threshold_sizes_match_oracle(seed):
         o.decode_step(z, z, z)
         assert g.lengths() == o.lengths()
         assert g.lengths()[1] <= T
+
+
+def test_decode_step_that_cannot_evict_fails_before_it_changes_anything():
+    """Alg. 1's eviction branch inside a decode step: when its survivors would not fit an explicit capacity the
+    step is refused as a whole -- no token appended, sizes unchanged, and a retry fails the same way."""
+    k, w, s, T = 2, 10, 4, 4
+    g = BuzzCache(cfg(sink=k, window=w, segment=s, keep=1, evict_every=T, old_stride=1, capacity=k + w + T + 6,
+                      max_context=1000))
+    g.prefill(None, None, n_prompt=k + w)
+    for _ in range(6 * T):                                     # six evictions fill the six old rows
+        g.decode_step(None, None, None, None)
+    assert g.lengths() == (k + 6 + w, 6, 0)
+    for _ in range(T - 1):
+        g.decode_step(None, None, None, None)
+    before = g.lengths()
+    assert before == (k + 6 + w + T - 1, 6, T - 1)
+    for _ in range(2):                                         # the step that would trigger the seventh eviction
+        with pytest.raises(BuzzError) as e:
+            g.decode_step(None, None, None, None)
+        assert e.value.code == -2
+        assert g.lengths() == before
