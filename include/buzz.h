@@ -155,6 +155,25 @@ int buzz_decode_step(buzz_cache_t* cache, const void* q, const void* k_new, cons
                      float* out, void* hip_stream);
 
 /*
+ * buzz_decode_step for callers that cannot allocate device memory or let a library do so on their
+ * behalf: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same results and same errors as buzz_decode_step; the difference is where the scratch
+ * of the split softmax lives (one arrival counter per (batch, kv-head) and one (max, sum, partial
+ * output) record per key-range split and query head): not in the caller's workspace but in an
+ * array inside the library's device image, 8.25 MiB per GPU, held until the process ends.  The call
+ * reaches no hipMalloc / hipFree and no allocating library routine, and clears the counters it uses
+ * with a small kernel (no memset node), whatever the previous call left there.
+ * Additional errors: BUZZ_ECAPACITY when batch * n_kv_heads * splits * group * (head_dim + 2) * 4
+ * bytes exceed 8 MiB (the split count follows from the shape as in buzz_decode_step;
+ * buzz_cache_set_splits lowers it); BUZZ_ESTATE while buzz_cache_profile is on (its events are
+ * created per launch).
+ * Every call on one GPU shares that GPU's array: calls whose kernels may overlap on one GPU (two
+ * streams, two threads) race, whichever caches they are for; calls on one stream are safe.
+ */
+int buzz_decode_step_static(buzz_cache_t* cache, const void* q, const void* k_new, const void* v_new,
+                            float* out, void* hip_stream);
+
+/*
  * One eviction (the eviction branch of Alg. 1, with Alg. 2): old rows are interval-sampled
  * with stride s^, the rows between old region and window are cut into
  * segments of s from their start (the last may be ragged) and the top

@@ -24,7 +24,8 @@ FLAG_DETERMINISTIC = 64
 FLAG_INTERVAL_NEW = 128
 DTYPE_CODES = {"fp32": 0, "fp16": 1, "bf16": 2}
 
-EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step", "buzz_evict",
+EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step",
+           "buzz_decode_step_static", "buzz_evict",
            "buzz_cache_destroy", "buzz_cache_len", "buzz_cache_export", "buzz_cache_set_splits", "buzz_cache_profile",
            "buzz_cache_profile_read", "buzz_bench_copy", "buzz_bench_pipes", "buzz_suggest_threshold", "buzz_strerror"]
 
@@ -97,6 +98,7 @@ def load_library():
     lib.buzz_cache_create.argtypes = [ctypes.POINTER(_Cfg), P, ctypes.c_size_t, ctypes.POINTER(P)]
     lib.buzz_prefill.argtypes = [P, P, P, I64, P, I64, P, P]
     lib.buzz_decode_step.argtypes = [P, P, P, P, P, P]
+    lib.buzz_decode_step_static.argtypes = [P, P, P, P, P, P]
     lib.buzz_evict.argtypes = [P, P]
     lib.buzz_cache_destroy.argtypes = [P]
     lib.buzz_cache_len.argtypes = [P, ctypes.POINTER(I64), ctypes.POINTER(I64), ctypes.POINTER(I64)]
@@ -193,6 +195,11 @@ class BuzzCache:
     def decode_step(self, q, k_new, v_new, out, stream=None):
         _check(self._lib.buzz_decode_step(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                           self._stream(stream)), "buzz_decode_step")
+
+    def decode_step_static(self, q, k_new, v_new, out, stream=None):
+        """``decode_step`` with the split-softmax scratch in the library's static device array (allocates nothing)."""
+        _check(self._lib.buzz_decode_step_static(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                                 self._stream(stream)), "buzz_decode_step_static")
 
     def evict(self, stream=None):
         _check(self._lib.buzz_evict(self._h, self._stream(stream)), "buzz_evict")

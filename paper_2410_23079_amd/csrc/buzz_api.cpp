@@ -9,7 +9,33 @@
 
 using namespace buzz;
 
+// Scratch of buzz_decode_step_static: the arrival counters and the per-split partial results of the split
+// softmax, for callers that must not allocate.  One copy per GPU, held until the process ends; every call
+// on a GPU shares it.  In host code this name is only a handle for hipGetSymbolAddress: the device address
+// is looked up once per device and kept in g_static_scratch[].
+constexpr size_t kStaticTicketBytes = 65536 * sizeof(int32_t);          // one counter per unit (units <= 65535)
+constexpr size_t kStaticPartialBytes = (size_t)8 << 20;                 // (max, sum) pairs and partial outputs
+constexpr size_t kStaticScratchBytes = kStaticTicketBytes + kStaticPartialBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices];   // device address of `scratch` on each GPU, nullptr until first use there
+
+// Device address of this GPU's copy of the static scratch array (looked up once per device).
+int static_scratch_ptr(char** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BUZZ_EHIP;
+    if (!g_static_scratch[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BUZZ_EHIP;
+        g_static_scratch[dev] = p;
+    }
+    *out = (char*)g_static_scratch[dev];
+    return BUZZ_OK;
+}
 
 constexpr uint32_t kMagic = 0xB0220C4Eu;
 
@@ -496,12 +522,19 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
     return BUZZ_OK;
 }
 
-int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const void* v_new, float* out,
-                     void* hip_stream)
+}  // extern "C"
+
+namespace {
+
+// One decode step.  static_scratch: the split-softmax scratch (arrival counters, per-split partials) is the
+// library's static device array instead of the caller's workspace.
+int decode_step_impl(buzz_cache_t* c, const void* q, const void* k_new, const void* v_new, float* out,
+                     void* hip_stream, bool static_scratch)
 {
     if (!alive(c)) return BUZZ_EINVAL;
     if (!c->dry && (!q || !k_new || !v_new || !out)) return BUZZ_EINVAL;
     if (!c->ready) return BUZZ_ESTATE;
+    if (static_scratch && c->prof) return BUZZ_ESTATE;         // the profiling pass creates events per launch
     const buzz_config_t& cfg = c->cfg;
     const Layout& L = c->L;
     if (c->tokens_seen >= cfg.max_context) return BUZZ_ECAPACITY;
@@ -569,9 +602,24 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
         }
         a.rows_per_split = (int32_t)rps;
         a.n_splits = (int32_t)ceil_div(n, rps);
+        if (static_scratch && a.n_splits > 1) {
+            // partials are laid out [units][n_splits] in the static array; the counters are cleared by a small
+            // kernel (not a memset: the caller may be capturing a graph), whatever the last call left there
+            const size_t ml_bytes = align_up((size_t)L.units * a.n_splits * L.G * 2 * sizeof(float), 256);
+            const size_t o_bytes = (size_t)L.units * a.n_splits * L.G * cfg.head_dim * sizeof(float);
+            if (ml_bytes + o_bytes > kStaticPartialBytes) return BUZZ_ECAPACITY;
+            char* sp = nullptr;
+            if (int rc = static_scratch_ptr(&sp)) return rc;
+            a.ticket = (int32_t*)sp;
+            a.part_ml = (float*)(sp + kStaticTicketBytes);
+            a.part_o = (float*)(sp + kStaticTicketBytes + ml_bytes);
+            a.s_cap = a.n_splits;
+            if (hipError_t e = launch_fill_f32((float*)sp, nullptr, L.units, st)) return hip_rc(e);
+        }
         // about 8 waves per compute unit; 4-wave blocks also where 8 waves' partial outputs would not fit the LDS
         a.waves = ((int64_t)L.units * a.n_splits <= cus && L.G * cfg.head_dim < kWideBlockMaxGD) ? 8 : 4;
-        if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st, prof_pair(c, 0)))
+        if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st,
+                                             static_scratch ? Timing{} : prof_pair(c, 0)))
             return hip_rc(e);
         if (c->prof) c->prof_row_bytes += (double)L.units * (double)n * 2.0 * L.row_bytes;
         c->last_buf = cur;
@@ -583,6 +631,22 @@ int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const vo
     if (evict_after || ((cfg.flags & BUZZ_FLAG_AUTO_EVICT) && c->trigger_count() >= cfg.evict_every))
         return evict_impl(c, st);                              // cannot fail for capacity: checked above
     return BUZZ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int buzz_decode_step(buzz_cache_t* c, const void* q, const void* k_new, const void* v_new, float* out,
+                     void* hip_stream)
+{
+    return decode_step_impl(c, q, k_new, v_new, out, hip_stream, false);
+}
+
+int buzz_decode_step_static(buzz_cache_t* c, const void* q, const void* k_new, const void* v_new, float* out,
+                            void* hip_stream)
+{
+    return decode_step_impl(c, q, k_new, v_new, out, hip_stream, true);
 }
 
 int buzz_evict(buzz_cache_t* c, void* hip_stream)

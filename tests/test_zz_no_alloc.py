@@ -1,0 +1,95 @@
+"""The entry point that allocates nothing (buzz_decode_step_static, split-softmax scratch in the library's
+static device array) against buzz_decode_step, through the C ABI: same inputs, same cache history.
+
+Bars: in deterministic mode the two entry points run the same kernels on the same rows in the same order, so
+outputs and final cache contents must be bit-identical; in the default mode (tiles claimed dynamically) the
+outputs must agree within 1e-5 and, like every decode step, within 2e-3 of the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import decode_inputs, get_workload, prompt_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(wl, flags, splits=0):
+    from paper_2410_23079_amd import BuzzCache
+    from tests import lockstep as ls
+    p, d = prompt_inputs(wl, device="cuda"), decode_inputs(wl, device="cuda")
+    caches = [BuzzCache(ls.buzz_config(wl, flags=flags)) for _ in range(2)]
+    for c in caches:
+        if splits:
+            c.set_splits(splits)
+        c.prefill(p["K"], p["V"], q_obs=p["q_obs"])
+    outs = [torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device="cuda") for _ in range(2)]
+    return p, d, caches, outs
+
+
+def _oracle(wl, p):
+    from oracle.buzz_oracle import OracleCache, OracleConfig
+    o = OracleCache(OracleConfig(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.sink, wl.window, wl.segment,
+                                 wl.keep, wl.evict_every, wl.old_stride, auto_evict=True))
+    o.prefill(p["K"].double().cpu().numpy(), p["V"].double().cpu().numpy(), q_obs=p["q_obs"].double().cpu().numpy())
+    return o
+
+
+BIG = dict(batch=1, n_kv_heads=4, n_q_heads=16, head_dim=128, dtype="bf16", prompt=6000, decode_steps=40,
+           sink=4, window=2000, segment=16, keep=2, evict_every=16, n_obs=32)      # ~20 splits per unit, matrix cores
+SMALL = dict(batch=1, n_kv_heads=2, n_q_heads=2, head_dim=64, dtype="fp16", prompt=700, decode_steps=40,
+             sink=2, window=300, segment=8, keep=1, evict_every=8, n_obs=8)        # 3 splits per unit, vector ALU
+
+
+@pytest.mark.parametrize("deterministic", [True, False])
+def test_static_scratch_step_matches_the_workspace_step(deterministic):
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_DETERMINISTIC
+    from tests import lockstep as ls
+    flags = FLAG_AUTO_EVICT | (FLAG_DETERMINISTIC if deterministic else 0)
+    big, small = get_workload("tiny").scaled(**BIG), get_workload("tiny").scaled(**SMALL)
+    runs = [(wl, *_pair(wl, flags)) for wl in (big, small)]
+    oracles = [_oracle(wl, p) for wl, p, _, _, _ in runs]
+    for t in range(big.decode_steps):
+        # two static calls in a row on one GPU, the second with the smaller input; then the reference calls
+        for wl, p, d, (ref, sta), (out_ref, out_sta) in runs:
+            print(f"[no-alloc] step {t} {wl.dtype} units {wl.batch * wl.n_kv_heads} G {wl.group} "
+                  f"rows {sta.lengths()[0] + 1}", flush=True)
+            sta.decode_step_static(d["q"][t], d["k"][t], d["v"][t], out_sta)
+        for wl, p, d, (ref, sta), (out_ref, out_sta) in runs:
+            ref.decode_step(d["q"][t], d["k"][t], d["v"][t], out_ref)
+        for (wl, p, d, (ref, sta), (out_ref, out_sta)), o in zip(runs, oracles):
+            if deterministic:
+                assert torch.equal(out_ref, out_sta), f"step {t}: outputs differ"
+            else:
+                e = ls.rel_err(out_sta.double().cpu().numpy(), out_ref.double().cpu().numpy())
+                assert e <= ls.REPRO_TOL, f"step {t}: outputs differ by {e}"
+            want = o.decode_step(*(d[x][t].double().cpu().numpy() for x in ("q", "k", "v")))
+            e = ls.rel_err(out_sta.double().cpu().numpy(), want)
+            assert e <= ls.OUT_TOL, f"step {t}: static-scratch output off the oracle by {e}"
+            assert ref.lengths() == sta.lengths()
+    for wl, p, d, (ref, sta), _ in runs:
+        assert wl.decode_steps // wl.evict_every >= 2                 # evictions happened on the way
+        for i, (x, y) in enumerate(zip(ref.export(), sta.export())):  # K, V, score, pos
+            if i == 2 and not deterministic:
+                assert torch.allclose(x, y, rtol=ls.REPRO_TOL, atol=ls.REPRO_TOL)
+            else:
+                assert torch.equal(x, y)
+        ref.close(); sta.close()
+
+
+def test_static_scratch_rejects_what_does_not_fit():
+    """128 units x 32 splits x 8 heads x (256 + 2) floats = 33.8 MB of partials against the array's 8 MiB."""
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, BuzzError
+    wl = get_workload("tiny").scaled(batch=16, n_kv_heads=8, n_q_heads=64, head_dim=256, dtype="bf16", prompt=2100,
+                                     decode_steps=4, sink=4, window=2500, segment=16, keep=1, evict_every=16, n_obs=0)
+    p, d, (ref, sta), (out_ref, out_sta) = _pair(wl, FLAG_AUTO_EVICT, splits=32)
+    before = sta.lengths()
+    with pytest.raises(BuzzError) as e:
+        sta.decode_step_static(d["q"][0], d["k"][0], d["v"][0], out_sta)
+    assert e.value.code == -2 and sta.lengths() == before
+    sta.set_splits(4)                                            # 128 x 4 x 8 x 258 x 4 B = 4.2 MB fits
+    ref.set_splits(4)
+    sta.decode_step_static(d["q"][0], d["k"][0], d["v"][0], out_sta)
+    ref.decode_step(d["q"][0], d["k"][0], d["v"][0], out_ref)
+    from tests import lockstep as ls
+    assert ls.rel_err(out_sta.double().cpu().numpy(), out_ref.double().cpu().numpy()) <= ls.REPRO_TOL
+    ref.close(); sta.close()
