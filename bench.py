@@ -3,10 +3,17 @@
 One "step" = one decode step of every layer: append, split decode attention over the retained cache,
 score accumulation, and the beehive eviction whenever T tokens have been buffered.  Inputs are seeded,
 synthetic and resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+The headline workload is the largest single-GPU one (`llama7b_full`: 32 layers, 33 GB of cache traffic per
+step, HBM-bound).  Whatever --steps / --warmup are, the caches are first rolled forward (untimed) to the
+point of the eviction cycle at which the timed steps contain ceil(steps / T) evictions, so the eviction cost
+is always inside the number.  Without --workload the line also carries compact sub-records of the other
+benchmark workloads (`others`), measured the same way.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -17,6 +24,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+DEFAULT_WORKLOAD = "llama7b_full"
+# (workload, force streaming K/V loads): the sub-records of a default run
+OTHERS = [("llama7b_layer", False), ("llama7b_layer", True), ("gqa8b_layer", False), ("long131k", False)]
+MAX_INPUT_STEPS = 512          # distinct decode inputs per stream; longer runs cycle through them (i.i.d. draws)
 
 
 def parse():
@@ -24,19 +35,17 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="llama7b_layer")
+    ap.add_argument("--workload", default=None, help=f"default {DEFAULT_WORKLOAD}, plus sub-records of the others")
     ap.add_argument("--layers", type=int, default=None, help="override the workload's layer count")
     ap.add_argument("--splits", type=int, default=0, help="key-range splits per unit (0 = automatic)")
     ap.add_argument("--streaming", action="store_true",
                     help="force streaming (non-temporal) K/V loads, as a cache that is one of many layers would use")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="no sub-records of the other workloads")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run the library's plain copy kernel once on this many MiB (for rocprofv3 --pmc runs: "
                          "its known size gives the scale of the byte counters)")
-    ap.add_argument("--pipe-probe", action="store_true",
-                    help="instead of a workload: time the matrix / vector instruction mix of the prompt-scoring "
-                         "kernels alone and print how far the two pipes overlap")
     ap.add_argument("--prefill-obs", type=int, default=0,
                     help="also time the prefill of one layer with this many observed prompt queries (prefill scoring; "
                          "off the decode metric) and report it as `prefill_scoring`")
@@ -70,20 +79,128 @@ def prefill_all(wl, caches, device):
 
 def step_views(dec):
     """Per decode-input stream, the (q, k, v) tensors of every step: slicing them inside the timed loop would
-    charge ~8 us of host time per step, more than config 1's whole kernel."""
+    charge ~8 us of host time per step, more than the smallest workload's whole kernel."""
     return [[(d["q"][t], d["k"][t], d["v"][t]) for t in range(d["q"].shape[0])] for d in dec]
 
 
-def run_steps(caches, views, out, first, count, stream):
-    for t in range(first, first + count):
-        for layer, c in enumerate(caches):
-            q, k, v = views[layer % len(views)][t]
-            c.decode_step(q, k, v, out, stream)
+class Runner:
+    """Drives the caches of one workload step by step and knows where in the eviction cycle they are."""
+
+    def __init__(self, wl, caches, views, out, stream):
+        self.wl, self.caches, self.views, self.out, self.stream = wl, caches, views, out, stream
+        self.done = 0                                   # decode steps since the prefill
+
+    def run(self, count):
+        n_in = len(self.views[0])
+        for t in range(self.done, self.done + count):
+            for layer, c in enumerate(self.caches):
+                q, k, v = self.views[layer % len(self.views)][t % n_in]
+                c.decode_step(q, k, v, self.out, self.stream)
+        self.done += count
+
+    def until_next_eviction(self):
+        """Decode steps left until the automatic eviction fires (it fires at the end of that step)."""
+        _, n_old, new = self.caches[0].lengths()
+        have = n_old + new if self.wl.threshold_total else new
+        return max(1, self.wl.evict_every - have)
+
+    def roll_for(self, steps):
+        """Untimed steps that bring the caches to the point of the eviction cycle from which the next `steps`
+        steps contain ceil(steps / T) evictions, the odd one in the middle of its share of the steps: the
+        eviction has to fire on step (r + 1) // 2 from here, r = steps mod T.  Returns (steps rolled, evictions
+        the next `steps` steps will contain)."""
+        T = self.wl.evict_every
+        r = steps % T
+        m = (r + 1) // 2 if r else self.until_next_eviction()   # r = 0: any alignment gives steps / T evictions
+        rolled = 0
+        while self.until_next_eviction() != m and rolled < 3 * T:   # (bounded: under the total-threshold reading
+            self.run(1)                                             # a cycle can be shorter than m)
+            rolled += 1
+        u = self.until_next_eviction()
+        period = T if not self.wl.threshold_total else None
+        expected = (0 if u > steps else (steps - u) // period + 1) if period else None
+        return rolled, expected
+
+
+def measure(wl, layers, steps, warmup, splits, streaming, device, profile, copy_mib=0):
+    """One workload: prefill, roll, warm up, K timed steps, then (optionally) K more steps with per-kernel
+    events.  Returns the measurements; frees the caches."""
+    import torch
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_STREAMING
+    from workloads import decode_inputs
+
+    T = wl.evict_every
+    budget = warmup + 2 * steps + 6 * T + 2            # decode steps both passes can take, rolls included
+    n_streams = min(layers, 4)                         # decode inputs: a few distinct seeded streams, reused over layers
+    dec = step_views([decode_inputs(wl, layer=i, device=device, steps=min(budget, MAX_INPUT_STEPS))
+                      for i in range(n_streams)])
+    stream = torch.cuda.current_stream().cuda_stream
+    out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device=device)
+    flags = FLAG_AUTO_EVICT | (FLAG_STREAMING if streaming else 0)
+    caches = make_caches(wl, layers, wl.prompt + budget, splits, flags)
+    prefill_all(wl, caches, device)
+    if copy_mib:
+        from paper_2410_23079_amd import bench_copy
+        src = torch.full((copy_mib << 20,), 7, dtype=torch.uint8, device=device)
+        dst = torch.empty_like(src)
+        bench_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+    run = Runner(wl, caches, dec, out, stream)
+
+    run.run(warmup)
+    rolled, timed_evictions = run.roll_for(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run.run(steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_end = caches[0].lengths()[0]
+    res = {"steps_per_s": steps / elapsed, "ms_per_step": elapsed / steps * 1e3, "rolled_steps": rolled,
+           "evictions_in_timed_steps": timed_evictions, "retained_rows_end": n_end}
+
+    # second pass: the next K steps, aligned the same way, with HIP events around every kernel (on the launch stream)
+    if profile:
+        run.roll_for(steps)
+        for c in caches:
+            c.profile(True)
+        run.run(steps)
+        torch.cuda.synchronize()
+        prof = [c.profile_read() for c in caches]
+        for c in caches:
+            c.profile(False)
+        launches = sum(p["attn_launches"] for p in prof)
+        attn_ms = sum(p["attn_ms"] for p in prof)
+        ev_ms = sum(p["evict_ms"] for p in prof) + sum(p["epilogue_ms"] for p in prof)
+        evictions = sum(p["evictions"] for p in prof)
+        kv_bytes = sum(p["attn_row_bytes"] for p in prof)            # sum over launches of units * n * 2 * D * e
+        units = wl.batch * wl.n_kv_heads
+        elem = 4 if wl.dtype == "fp32" else 2
+        rows = kv_bytes / (units * 2 * wl.head_dim * elem)           # sum over launches of n
+        # algorithmic bytes of the attention + score pass: K and V rows plus the fp32 score read and write
+        algo_bytes = kv_bytes + units * rows * 8.0
+        achieved = algo_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms else 0.0
+        attn_us = attn_ms * 1e3 / max(launches, 1)
+        evict_us_per_step = ev_ms * 1e3 / steps / layers             # amortised, per layer
+        res.update({
+            "kernel": "attn_split_mfma_kernel" if (wl.group > 1 and wl.dtype != "fp32") else "attn_split_kernel",
+            "achieved_gbs": achieved, "frac": achieved / HBM_PEAK_GBS, "avg_launch_us": attn_us, "launches": launches,
+            "bytes_per_launch": algo_bytes / max(launches, 1),
+            "evictions": evictions // layers, "evict_avg_us": ev_ms * 1e3 / max(evictions, 1),
+            "evict_us_per_step": evict_us_per_step,
+            "evict_share_of_step": evict_us_per_step / (attn_us + evict_us_per_step) if attn_us else 0.0,
+            # what one layer's step costs beyond its kernels: launch latency and host time not hidden by the GPU
+            "launch_gap_us": elapsed / steps / layers * 1e6 - attn_us - evict_us_per_step,
+        })
+    res["_caches"] = caches                                         # the caller may still want one (prefill scoring)
+    return res
 
 
 def prefill_scoring(wl, cache, n_obs, device, reps=3):
     """Time of one layer's prefill with and without scoring by the last n_obs prompt queries.  The difference is
-    the two scoring kernels; their work is 2 x 2 D flops per (query, visible key) pair and query head."""
+    the two scoring kernels.  The method's own contraction is q.k for every causal (query, key) pair: 2 D flops
+    per pair and query head; the kernels form every logit twice (row statistics, then probabilities), so the
+    matrix cores do twice that."""
     import torch
     from workloads import prompt_inputs
     p = prompt_inputs(wl.scaled(n_obs=n_obs), device=device)
@@ -101,28 +218,29 @@ def prefill_scoring(wl, cache, n_obs, device, reps=3):
     with_scoring, without = timed(q_obs), timed(None)
     N = wl.prompt
     pairs = n_obs * (N - n_obs) + n_obs * (n_obs + 1) / 2             # causal (query, key) pairs per head
-    flops = 4.0 * wl.head_dim * pairs * wl.batch * wl.n_q_heads
+    flops = 2.0 * wl.head_dim * pairs * wl.batch * wl.n_q_heads       # the method's contraction, once
     dt = max(with_scoring - without, 1e-9)
     mfma = wl.dtype != "fp32"
     peak = 2500.0 if mfma else 157.3
     return {"n_obs": n_obs, "prefill_ms": with_scoring * 1e3, "prefill_without_scoring_ms": without * 1e3,
             "scoring_ms": dt * 1e3, "flops": flops, "achieved": flops / dt / 1e12, "unit": "TFLOP/s",
-            "bound": "mfma" if mfma else "alu", "peak": peak, "frac": flops / dt / 1e12 / peak}
+            "bound": "mfma" if mfma else "alu", "peak": peak, "frac": flops / dt / 1e12 / peak,
+            "frac_counting_both_passes": 2.0 * flops / dt / 1e12 / peak}
 
 
-def cpu_baseline(wl, budget_s=20.0):
-    """The oracle as it stands, on the host cores, on a bounded sample: one layer, every (batch, kv-head) unit,
-    prompt scores left at zero (prefill is not part of the metric), decode steps until the time budget is used."""
-    import numpy as np
-    from oracle.buzz_oracle import OracleCache, OracleConfig, _load
+def cpu_baseline(wl, budget_s=12.0):
+    """The oracle as it stands, on the host cores, on a bounded sample: one layer, a subset of the (batch,
+    kv-head) units, prompt scores left at zero (prefill is not part of the metric), decode steps for about
+    `budget_s` seconds and at least one eviction period."""
+    from oracle.buzz_oracle import OracleCache, OracleConfig
     from workloads import decode_inputs, prompt_inputs
-    B = wl.batch                                       # bound host memory (fp64 copies of the prompt) to ~4 GB:
-    while B > 1 and B * wl.n_kv_heads * wl.prompt * wl.head_dim * 16 > (4 << 30):
+    B = wl.batch                                       # bound host memory (fp64 copies of the prompt) to ~2 GB:
+    while B > 1 and B * wl.n_kv_heads * wl.prompt * wl.head_dim * 16 > (2 << 30):
         B //= 2                                        # units are independent and identical in cost
     sub = wl.scaled(batch=B)
     p = prompt_inputs(sub, device="cpu")
-    steps = sub.decode_steps
-    d = decode_inputs(sub, device="cpu", steps=steps)
+    n_in = min(sub.decode_steps, MAX_INPUT_STEPS)
+    d = decode_inputs(sub, device="cpu", steps=n_in)
     o = OracleCache(OracleConfig(sub.batch, sub.n_q_heads, sub.n_kv_heads, sub.head_dim, sub.sink, sub.window,
                                  sub.segment, sub.keep, sub.evict_every, sub.old_stride,
                                  threshold_total=sub.threshold_total))
@@ -130,8 +248,8 @@ def cpu_baseline(wl, budget_s=20.0):
     del p
     q, k, v = (d[x].double().numpy() for x in ("q", "k", "v"))
     done, t0 = 0, time.perf_counter()
-    while done < steps and (time.perf_counter() - t0 < budget_s or done < sub.evict_every):
-        o.decode_step(q[done], k[done], v[done])
+    while time.perf_counter() - t0 < budget_s or done < sub.evict_every:
+        o.decode_step(q[done % n_in], k[done % n_in], v[done % n_in])
         done += 1
     dt = time.perf_counter() - t0
     frac = (sub.batch * sub.n_kv_heads) / (wl.batch * wl.n_kv_heads)
@@ -143,26 +261,18 @@ def cpu_baseline(wl, budget_s=20.0):
                       f"scaled by units and {wl.layers} layer(s)"}
 
 
-def pipe_probe(iters=20000, clock_ghz=2.4):
-    """Cycles (at the nominal clock) a SIMD needs per 16 x 64 tile of the prompt-scoring instruction mix: its 16
-    MFMAs alone, its 48 vector instructions alone, both; 1, 2 and 3 waves per SIMD (256, 512, 768 blocks)."""
+def release(res):
     import torch
-    from paper_2410_23079_amd import bench_pipes
-    torch.cuda.set_device(0)
-    out = torch.empty(768 * 256, dtype=torch.float32, device="cuda:0")
-    res = {}
-    for blocks in (256, 512, 768):
-        waves = blocks * 4 / 1024
-        for name, work in (("mfma", 1), ("vector", 2), ("both", 3)):
-            bench_pipes(work, blocks, 100, out)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            bench_pipes(work, blocks, iters, out)
-            e1.record()
-            e1.synchronize()
-            res[f"{name}_cycles_per_tile_{int(waves)}_waves_per_simd"] = round(
-                e0.elapsed_time(e1) * 1e-3 * clock_ghz * 1e9 / (iters * waves), 1)
-    return res
+    for c in res.pop("_caches", []):
+        c.close()
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def default_counts(wl, steps, warmup):
+    w = warmup if warmup is not None else min(64, wl.decode_steps // 8)
+    s = steps if steps is not None else wl.decode_steps - w
+    return s, w
 
 
 def main():
@@ -172,68 +282,19 @@ def main():
               "batch and kv heads); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_STREAMING
-    from workloads import decode_inputs, get_workload
+    from workloads import get_workload
 
-    if args.pipe_probe:
-        print(json.dumps({"pipe_probe": pipe_probe()}), flush=True)
-        return
-    wl = get_workload(args.workload)
+    wl = get_workload(args.workload or DEFAULT_WORKLOAD)
     layers = args.layers or wl.layers
-    warmup = args.warmup if args.warmup is not None else min(64, wl.decode_steps // 8)
-    steps = args.steps if args.steps is not None else wl.decode_steps - warmup
-    total = warmup + steps
+    steps, warmup = default_counts(wl, args.steps, args.warmup)
     device = "cuda:0"
     torch.cuda.set_device(0)
 
-    n_streams = min(layers, 4)                          # decode inputs: a few distinct seeded streams, reused over layers
-    dec = step_views([decode_inputs(wl, layer=i, device=device, steps=total) for i in range(n_streams)])
-    stream = torch.cuda.current_stream().cuda_stream
-    out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device=device)
-    flags = FLAG_AUTO_EVICT | (FLAG_STREAMING if args.streaming else 0)
-    caches = make_caches(wl, layers, wl.prompt + total, args.splits, flags)
-    prefill_all(wl, caches, device)
-
-    if args.copy_calibration_mib:
-        from paper_2410_23079_amd import bench_copy
-        src = torch.full((args.copy_calibration_mib << 20,), 7, dtype=torch.uint8, device=device)
-        dst = torch.empty_like(src)
-        bench_copy(dst, src)
-        torch.cuda.synchronize()
-        del src, dst
-    run_steps(caches, dec, out, 0, warmup, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(caches, dec, out, warmup, steps, stream)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    n_end = caches[0].lengths()[0]
-
-    # second pass, same steps, with HIP events around every kernel (on the launch stream)
+    res = measure(wl, layers, steps, warmup, args.splits, args.streaming, device, not args.no_profile_pass,
+                  copy_mib=args.copy_calibration_mib)
     roofline = None
     extra = {}
     if not args.no_profile_pass:
-        prefill_all(wl, caches, device)
-        run_steps(caches, dec, out, 0, warmup, stream)
-        for c in caches:
-            c.profile(True)
-        run_steps(caches, dec, out, warmup, steps, stream)
-        torch.cuda.synchronize()
-        prof = [c.profile_read() for c in caches]
-        for c in caches:
-            c.profile(False)
-        launches = sum(p["attn_launches"] for p in prof)
-        attn_ms = sum(p["attn_ms"] for p in prof)
-        flush_ms = sum(p["epilogue_ms"] for p in prof)
-        ev_ms = sum(p["evict_ms"] for p in prof)
-        evictions = sum(p["evictions"] for p in prof)
-        kv_bytes = sum(p["attn_row_bytes"] for p in prof)            # sum over launches of units * n * 2 * D * e
-        units = wl.batch * wl.n_kv_heads
-        elem = 4 if wl.dtype == "fp32" else 2
-        rows = kv_bytes / (units * 2 * wl.head_dim * elem)           # sum over launches of n
-        # algorithmic bytes of the attention + score pass: K and V rows plus the fp32 score read and write
-        algo_bytes = kv_bytes + units * rows * 8.0
-        achieved = algo_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms else 0.0
         traffic = None                                             # HBM bytes per launch from rocprofv3 --pmc runs
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
         if os.path.exists(tpath):
@@ -241,34 +302,47 @@ def main():
             if t and layers == wl.layers and not args.splits:
                 traffic = {"fetch_bytes": t["fetch_bytes_per_launch"], "write_bytes": t["write_bytes_per_launch"],
                            "source": t["source"]}
-        kname = "attn_split_mfma_kernel" if (wl.group > 1 and wl.dtype != "fp32") else "attn_split_kernel"
-        roofline = {"bound": "hbm", "kernel": kname, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "avg_launch_us": attn_ms * 1e3 / max(launches, 1), "launches": launches,
-                    "bytes_per_launch": algo_bytes / max(launches, 1), "traffic": traffic}
-        extra = {"evictions": evictions,
-                 "evict_avg_us": (ev_ms + flush_ms) * 1e3 / max(evictions, 1),
-                 "evict_time_over_attn_time": (ev_ms + flush_ms) / attn_ms if attn_ms else 0.0,
-                 "step_bytes_over_peak_over_step_time": (algo_bytes / max(launches, 1) * layers / HBM_PEAK_GBS / 1e9)
-                                                        / (elapsed / steps)}
-
+        roofline = {"bound": "hbm", "kernel": res["kernel"], "achieved": res["achieved_gbs"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": res["frac"], "avg_launch_us": res["avg_launch_us"],
+                    "launches": res["launches"], "bytes_per_launch": res["bytes_per_launch"], "traffic": traffic}
+        extra = {k: res[k] for k in ("evictions", "evict_avg_us", "evict_us_per_step", "evict_share_of_step",
+                                     "launch_gap_us")}
+        extra["step_bytes_over_peak_over_step_time"] = (res["bytes_per_launch"] * layers / HBM_PEAK_GBS / 1e9) \
+            / (res["ms_per_step"] * 1e-3)
+    extra["evictions_in_timed_steps"] = res["evictions_in_timed_steps"]
+    extra["rolled_steps"] = res["rolled_steps"]
     if args.prefill_obs:
-        extra["prefill_scoring"] = prefill_scoring(wl, caches[0], min(args.prefill_obs, wl.prompt), device)
+        extra["prefill_scoring"] = prefill_scoring(wl, res["_caches"][0], min(args.prefill_obs, wl.prompt), device)
+    n_end = res["retained_rows_end"]
+    release(res)
+
+    others = None
+    if args.workload is None and not args.no_others:
+        others = []
+        for name, streaming in OTHERS:
+            owl = get_workload(name)
+            osteps, owarm = default_counts(owl, None, None)
+            r = measure(owl, owl.layers, osteps, owarm, 0, streaming, device, True)
+            release(r)
+            others.append({"workload": name, "kv_loads": "streaming" if streaming else "auto", "steps": osteps,
+                           "warmup": owarm, **{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}})
 
     base = None if args.no_cpu_baseline else cpu_baseline(wl)
     line = {
-        "metric": "decode_steps_per_sec_incl_eviction", "value": steps / elapsed, "unit": "steps/s", "n_gpus": 1,
-        "steps": steps, "warmup": warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
+        "metric": "decode_steps_per_sec_incl_eviction", "value": res["steps_per_s"], "unit": "steps/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": f"{wl.dtype} storage, f32 accumulate", "data": "synthetic",
-        "tokens_per_s": steps / elapsed * wl.batch,
+        "tokens_per_s": res["steps_per_s"] * wl.batch,
         "config": {"workload": wl.name, "layers": layers, "batch": wl.batch, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "prompt": wl.prompt, "sink": wl.sink,
                    "window": wl.window, "segment": wl.segment, "keep": wl.keep, "evict_every": wl.evict_every,
-                   "old_stride": wl.old_stride, "threshold_total": wl.threshold_total, "retained_rows_end": n_end, "splits": args.splits or "auto",
-                   "kv_loads": "streaming" if args.streaming else "auto"},
+                   "old_stride": wl.old_stride, "threshold_total": wl.threshold_total, "retained_rows_end": n_end,
+                   "splits": args.splits or "auto", "kv_loads": "streaming" if args.streaming else "auto"},
         "roofline": roofline, "cpu_baseline": base,
     }
     line.update(extra)
+    if others is not None:
+        line["others"] = others
     print(json.dumps(line), flush=True)
 
 
