@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--splits", type=int, default=0, help="key-range splits per unit (0 = automatic)")
     ap.add_argument("--streaming", action="store_true",
                     help="force streaming (non-temporal) K/V loads, as a cache that is one of many layers would use")
+    ap.add_argument("--device-merge", action="store_true",
+                    help="merge a unit's splits through device memory even where its blocks can share a die")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="no sub-records of the other workloads")
@@ -122,11 +124,11 @@ class Runner:
         return rolled, expected
 
 
-def measure(wl, layers, steps, warmup, splits, streaming, device, profile, copy_mib=0):
+def measure(wl, layers, steps, warmup, splits, streaming, device, profile, copy_mib=0, device_merge=False):
     """One workload: prefill, roll, warm up, K timed steps, then (optionally) K more steps with per-kernel
     events.  Returns the measurements; frees the caches."""
     import torch
-    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_STREAMING
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_DEVICE_MERGE, FLAG_STREAMING
     from workloads import decode_inputs
 
     T = wl.evict_every
@@ -136,7 +138,7 @@ def measure(wl, layers, steps, warmup, splits, streaming, device, profile, copy_
                       for i in range(n_streams)])
     stream = torch.cuda.current_stream().cuda_stream
     out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device=device)
-    flags = FLAG_AUTO_EVICT | (FLAG_STREAMING if streaming else 0)
+    flags = FLAG_AUTO_EVICT | (FLAG_STREAMING if streaming else 0) | (FLAG_DEVICE_MERGE if device_merge else 0)
     caches = make_caches(wl, layers, wl.prompt + budget, splits, flags)
     prefill_all(wl, caches, device)
     if copy_mib:
@@ -291,7 +293,7 @@ def main():
     torch.cuda.set_device(0)
 
     res = measure(wl, layers, steps, warmup, args.splits, args.streaming, device, not args.no_profile_pass,
-                  copy_mib=args.copy_calibration_mib)
+                  copy_mib=args.copy_calibration_mib, device_merge=args.device_merge)
     roofline = None
     extra = {}
     if not args.no_profile_pass:
@@ -337,7 +339,8 @@ def main():
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "prompt": wl.prompt, "sink": wl.sink,
                    "window": wl.window, "segment": wl.segment, "keep": wl.keep, "evict_every": wl.evict_every,
                    "old_stride": wl.old_stride, "threshold_total": wl.threshold_total, "retained_rows_end": n_end,
-                   "splits": args.splits or "auto", "kv_loads": "streaming" if args.streaming else "auto"},
+                   "splits": args.splits or "auto", "kv_loads": "streaming" if args.streaming else "auto",
+                   "split_merge": "device" if args.device_merge else "auto"},
         "roofline": roofline, "cpu_baseline": base,
     }
     line.update(extra)

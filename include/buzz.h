@@ -73,7 +73,12 @@ enum {
     /* Ablation "no local max" (Sec. 4.4): new tokens are interval-sampled like old ones -- the first `keep`
        rows of every segment survive whatever their scores.  (The other ablation of that section, swapped
        strides, needs no flag: segment = s^ and old_stride = s.) */
-    BUZZ_FLAG_INTERVAL_NEW = 128u
+    BUZZ_FLAG_INTERVAL_NEW = 128u,
+    /* Where the key range of a (batch, kv-head) pair is split over several blocks and the pairs divide evenly
+       over the GPU's 8 dies, the blocks of a pair are placed on one die and exchange their partial results
+       through that die's L2.  With this flag they always exchange them through device memory instead (the
+       path taken anyway for other shapes).  Results are the same; meant for comparison. */
+    BUZZ_FLAG_DEVICE_MERGE = 256u
 };
 
 /* Symbols follow the paper's notation table (Sec. 3.3). */

@@ -149,16 +149,53 @@ template <int LPR> __device__ inline float row_sum(float v) {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Split partials travel between blocks (possibly on different XCDs, each with its own L2) inside one
-// launch.  They are written and read with device-scope atomic accesses, which go through to the
-// memory side instead of staying in an XCD's L2, so no cache write-back or invalidate is needed.
-__device__ inline void publish(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ inline float acquire(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// How split partials travel between the blocks of one launch (finish_split_scoped).
+//
+// Device-wide form (blocks of a unit possibly on different dies, each die with its own L2).  A block writes
+// its partial with relaxed device-scope atomic stores (`sc1`: written through the die's L2 to the memory
+// side), every wave waits with s_waitcnt vmcnt(0) for its own stores, the block synchronises, one thread takes
+// a ticket (relaxed atomic add), and the block that draws the last ticket reads every partial with relaxed
+// device-scope atomic loads (`sc1`: not served from a die's private copy).  Why the merging block cannot see a
+// stale partial: this is the compiler's own release / acquire sequence for device scope on this target with
+// the two cache-wide operations taken out, and neither is needed here.
+//   * Release side.  The documented release sequence is "write back the L2 (buffer_wbl2 sc1), then
+//     s_waitcnt vmcnt(0), then the releasing atomic".  vmcnt counts a store until the level that the store's
+//     scope names has acknowledged it; that is what makes the wait the completion point of the sequence, and
+//     for an sc1 store the acknowledgement comes from the memory side.  The write-back exists for data written
+//     earlier with weaker scope that may still sit dirty in the L2; every byte of a partial is written with an
+//     sc1 store, so there is nothing to write back.  (A device-scope fence here costs a full L2 write-back per
+//     block: 2.5-30x on the whole kernel.)  The wait is per wave, so every wave executes it before the block
+//     barrier, and only after the barrier does thread 0 take the ticket: the ticket is ordered after the
+//     acknowledgement of every store of the block.  Without the explicit wait the compiler is free to let the
+//     relaxed stores drain later, and the ticket then overtook a partial about once in 10^5 launches.
+//   * Acquire side.  The documented acquire sequence is "the acquiring atomic, then invalidate L1 and the
+//     non-local L2 lines (buffer_inv sc1)", so that LATER ORDINARY loads cannot hit stale copies.  The merging
+//     block reads the partials with sc1 atomic loads, which are coherent at device scope by themselves, so no
+//     invalidate is needed.  They cannot start early: the ticket's value goes through LDS and a block barrier
+//     to every thread, the loads are control-dependent on it (`last`), and a workgroup-scope acquire fence
+//     sits between the barrier and the loads, across which the compiler may not move atomic accesses.
+//   * The ticket itself is one atomic counter per unit; read-modify-write atomics execute at the point of
+//     coherence of their address whatever cache holds a copy.  The merging block resets it for the next launch.
+// Nobody waits for anybody: a block that is not last simply ends.
+//
+// Die-local form (LOCAL = true).  When all blocks of a unit run on ONE die (the host arranges that by block
+// number where the shape allows, see make_ctx), the same handshake runs one level lower: workgroup-scope
+// atomic stores and loads (`sc0`: through the compute unit's L1, served by the die's L2, which all its compute
+// units share), the same wait, the same ticket.  The hardware argument is the same with "the die's L2" in
+// place of "the memory side".  It lies outside the language memory model, which knows no scope between one
+// workgroup and the device, so it is guarded twice: the host enables it only on a GPU where a probe launch
+// has shown that block numbers equal mod 8 share a die, and every block compares the die it actually runs on
+// with the probe's record and flags a difference in the ticket, which turns the unit's output into NaN.
+// BUZZ_FLAG_DEVICE_MERGE selects the device-wide form everywhere.
+template <bool LOCAL> constexpr int merge_scope() { return LOCAL ? __HIP_MEMORY_SCOPE_WORKGROUP : __HIP_MEMORY_SCOPE_AGENT; }
+template <bool LOCAL> __device__ inline void publish(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, merge_scope<LOCAL>()); }
+template <bool LOCAL> __device__ inline float acquire(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, merge_scope<LOCAL>()); }
 
 // Where a block works: logical rows [j0, j1) of one unit.  The range is cut into at most four physically
 // contiguous runs (linear region, ring before the wrap, ring after the wrap, the row being appended).
 struct SplitCtx {
     int split, unit, b, kvh;
+    int home;            // die-local merge: launch-order block number mod 8, which decides the die
     int j0, j1, jl1, wrap;
     size_t ubase;
 };
@@ -167,6 +204,16 @@ __device__ inline SplitCtx make_ctx(const AttnArgs& a)
 {
     SplitCtx x;
     x.split = blockIdx.x; x.unit = blockIdx.y;
+    x.home = 0;
+    if (a.xcd_local) {
+        // The hardware deals the blocks of a grid to the dies (XCDs) round-robin in launch order: block b runs
+        // on die b mod 8.  Renumber so that the n_splits blocks of a unit share b mod 8 (units is a multiple of
+        // 8 here): die d gets units d * units/8 ... and, in launch order, their splits.
+        const int b = blockIdx.y * gridDim.x + blockIdx.x, die = b & 7, slot = b >> 3;
+        x.unit = die * (gridDim.y >> 3) + slot / (int)gridDim.x;
+        x.split = slot % (int)gridDim.x;
+        x.home = die;
+    }
     x.b = x.unit / a.Hkv; x.kvh = x.unit - x.b * a.Hkv;
     x.j0 = x.split * a.rows_per_split;
     x.j1 = min(a.n, x.j0 + a.rows_per_split);
@@ -307,8 +354,8 @@ __device__ inline void first_pass_scores(const AttnArgs& a, const SplitCtx& x, c
     }
 }
 
-template <int G, int D, int NW>
-__device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const PrevStat<G>& prev,
+template <int G, int D, int NW, bool LOCAL>
+__device__ inline void finish_split_scoped(const AttnArgs& a, const SplitCtx& x, const PrevStat<G>& prev,
                                     const float4 (&pre_sc)[3], const float* stage,
                                     float (*sm_m)[G], float (*sm_l)[G], float (*sm_acc)[G][D], int* sm_ticket)
 {
@@ -346,10 +393,10 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
                 a.stat[((size_t)unit * G + g) * 2 + 1] = 1.0f / L;
             }
         } else {
-            publish(a.part_o + (pbase + g) * D + d, o);
+            publish<LOCAL>(a.part_o + (pbase + g) * D + d, o);
             if (d == 0) {
-                publish(a.part_ml + (pbase + g) * 2, M);
-                publish(a.part_ml + (pbase + g) * 2 + 1, L);
+                publish<LOCAL>(a.part_ml + (pbase + g) * 2, M);
+                publish<LOCAL>(a.part_ml + (pbase + g) * 2 + 1, L);
             }
         }
     }
@@ -357,17 +404,25 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
     if (tid == 0) BUZZ_STAMP(2);
 
     // 3. ticket: the block that arrives last for this unit sees every split's partial.  Every wave first
-    // waits until its own published (write-through) stores have been acknowledged (vmcnt(0)), then the
-    // block synchronises, then one thread takes the ticket: the ticket can never overtake a partial.
-    // No cache maintenance is involved.
+    // waits until its own published stores have been acknowledged (vmcnt(0)), then the block synchronises,
+    // then one thread takes the ticket: the ticket can never overtake a partial (the argument is written out
+    // above merge_scope).  No cache maintenance is involved.
     bool last = false;
     if (S > 1) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0), expcnt / lgkmcnt untouched
         __syncthreads();
-        if (tid == 0) *sm_ticket = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) {
+            // A die-local merge is only right if this block really runs where its number says: the host has
+            // recorded which die served block numbers 0..7 (die_map, 4 bits each); a block that finds itself
+            // elsewhere says so in the ticket's upper half, and the merging block sees every earlier arrival's.
+            int add = 1;
+            if (LOCAL && (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u) != ((a.die_map >> (4 * x.home)) & 7u)) add += 0x10000;   // XCC_ID
+            const int before = __hip_atomic_fetch_add(a.ticket + unit, add, __ATOMIC_RELAXED, merge_scope<LOCAL>());
+            *sm_ticket = before + (add & 0x10000);
+        }
         __syncthreads();
-        last = *sm_ticket == S - 1;
+        last = (*sm_ticket & 0xffff) == S - 1;
         if (tid == 0) BUZZ_STAMP(4);
     }
 
@@ -392,8 +447,8 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
 #pragma unroll
             for (int e = 0; e < CH; ++e) {
                 const int sp = min(s0 + e, S - 1);
-                mlr[r][e] = __hip_atomic_load(ml + sp * G + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                xr[r][e] = acquire(po + (size_t)sp * G * D + i);
+                mlr[r][e] = __hip_atomic_load(ml + sp * G + g, __ATOMIC_RELAXED, merge_scope<LOCAL>());
+                xr[r][e] = acquire<LOCAL>(po + (size_t)sp * G * D + i);
             }
         }
     };
@@ -457,7 +512,10 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
     if (tid == 0) BUZZ_STAMP(3);
     if (!merger) return;
 
-    // 6. merge the splits: a running (max, sum, output) per owned element, CH splits per round
+    // 6. merge the splits: a running (max, sum, output) per owned element, CH splits per round.
+    // A die-local merge with a block on an unexpected die may have missed partials: its output is NaN rather
+    // than plausible numbers.
+    const float poison = (*sm_ticket >> 16) ? __builtin_nanf("") : 0.f;
     float Mr[OPT], Lr[OPT], Or[OPT];
 #pragma unroll
     for (int r = 0; r < OPT; ++r) { Mr[r] = -INFINITY; Lr[r] = 0.f; Or[r] = 0.f; }
@@ -486,14 +544,23 @@ __device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const 
         const int i = tid - NM + NM * r;
         if (i >= G * D) continue;
         const int g = i / D;
-        outp[i] = Or[r] / Lr[r];
+        outp[i] = Or[r] / Lr[r] + poison;
         if (i - g * D == 0) {
             a.stat[((size_t)unit * G + g) * 2] = Mr[r];
             a.stat[((size_t)unit * G + g) * 2 + 1] = 1.0f / Lr[r];
         }
     }
-    if (tid == NM) __hip_atomic_store(a.ticket + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next step
+    if (tid == NM) __hip_atomic_store(a.ticket + unit, 0, __ATOMIC_RELAXED, merge_scope<LOCAL>());   // ready for the next step
     if (tid == NM) BUZZ_STAMP(5);
+}
+
+template <int G, int D, int NW>
+__device__ inline void finish_split(const AttnArgs& a, const SplitCtx& x, const PrevStat<G>& prev,
+                                    const float4 (&pre_sc)[3], const float* stage,
+                                    float (*sm_m)[G], float (*sm_l)[G], float (*sm_acc)[G][D], int* sm_ticket)
+{
+    if (a.xcd_local) finish_split_scoped<G, D, NW, true>(a, x, prev, pre_sc, stage, sm_m, sm_l, sm_acc, sm_ticket);
+    else finish_split_scoped<G, D, NW, false>(a, x, prev, pre_sc, stage, sm_m, sm_l, sm_acc, sm_ticket);
 }
 
 // Vector-ALU streaming kernel (any dtype; the choice for one query head per kv head).

@@ -37,6 +37,56 @@ int static_scratch_ptr(char** out)
     return BUZZ_OK;
 }
 
+// Which die (XCD) a block runs on, for every block of a small 2-D grid: the evidence for placing a unit's
+// splits on one die by block number (see die_local_ok).
+__global__ void die_probe_kernel(int32_t* out)
+{
+    if (threadIdx.x == 0)
+        out[blockIdx.y * gridDim.x + blockIdx.x] = (int32_t)(__builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u);   // XCC_ID
+}
+
+int g_die_local[kMaxDevices];          // per GPU: 0 not probed yet, 1 blocks b and b + 8 share a die, 2 they do not
+uint32_t g_die_map[kMaxDevices];       // per GPU: the die of block numbers 0..7, 4 bits each
+
+// The die-local merge of the decode kernel relies on the hardware dealing the blocks of a grid to the dies
+// round-robin in launch order (block b on die b mod 8), so that blocks whose numbers agree mod 8 share a die
+// and its L2.  This checks that property once per GPU and process on two grid shapes, with one synchronisation
+// of `st`; where it does not hold the decode step merges through device memory as it does for other shapes.
+// Called from the prefill (never from a decode step, which must not synchronise).
+int probe_die_placement(hipStream_t st)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BUZZ_EHIP;
+    if (g_die_local[dev]) return BUZZ_OK;
+    char* sp = nullptr;
+    if (int rc = static_scratch_ptr(&sp)) return rc;
+    int32_t* buf = (int32_t*)(sp + kStaticTicketBytes);                  // the partials area of the static scratch
+    constexpr int kA = 8 * 64, kB = 3 * 40;
+    int32_t host[kA + kB];
+    hipLaunchKernelGGL(die_probe_kernel, dim3(8, 64), dim3(64), 0, st, buf);
+    hipLaunchKernelGGL(die_probe_kernel, dim3(3, 40), dim3(64), 0, st, buf + kA);
+    if (hipGetLastError() != hipSuccess) return BUZZ_EHIP;
+    if (hipMemcpyAsync(host, buf, sizeof(host), hipMemcpyDeviceToHost, st) != hipSuccess) return BUZZ_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return BUZZ_EHIP;
+    bool ok = true;
+    for (int b = 8; b < kA; ++b) ok &= host[b] == host[b & 7];
+    for (int b = 8; b < kB; ++b) ok &= host[kA + b] == host[kA + (b & 7)];
+    uint32_t map = 0;
+    for (int b = 0; b < 8; ++b) map |= (uint32_t)(host[b] & 7) << (4 * b);
+    g_die_map[dev] = map;
+    g_die_local[dev] = ok ? 1 : 2;
+    return BUZZ_OK;
+}
+
+// Whether this GPU passed the placement probe; *map = the die of block numbers 0..7.
+bool die_local_ok(uint32_t* map)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices || g_die_local[dev] != 1) return false;
+    *map = g_die_map[dev];
+    return true;
+}
+
 constexpr uint32_t kMagic = 0xB0220C4Eu;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -58,7 +108,7 @@ int make_layout(const buzz_config_t* c, Layout* L)
     if (c->old_stride < 0 || c->max_context < 1 || c->capacity < 0 || c->reserved != 0) return BUZZ_EINVAL;
     if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN | BUZZ_FLAG_STREAMING | BUZZ_FLAG_CACHED |
                               BUZZ_FLAG_LOG_N | BUZZ_FLAG_THRESHOLD_TOTAL | BUZZ_FLAG_DETERMINISTIC |
-                              BUZZ_FLAG_INTERVAL_NEW))
+                              BUZZ_FLAG_INTERVAL_NEW | BUZZ_FLAG_DEVICE_MERGE))
         return BUZZ_EINVAL;
     if ((c->flags & BUZZ_FLAG_STREAMING) && (c->flags & BUZZ_FLAG_CACHED)) return BUZZ_EINVAL;
     if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BUZZ_EINVAL;
@@ -453,6 +503,7 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
 
     if (!c->dry) {
         float* ps = c->at<float>(L.pscore);
+        if (int rc = probe_die_placement(st)) return rc;
         if (hipError_t e = launch_fill_f32(c->at<float>(L.ticket), nullptr, L.units, st)) return hip_rc(e);
         // starting scores, one row of N per unit
         if (hipError_t e = launch_fill_f32(ps, init_score, (int64_t)L.units * N, st)) return hip_rc(e);
@@ -567,7 +618,8 @@ int decode_step_impl(buzz_cache_t* c, const void* q, const void* k_new, const vo
         const int cur = c->last_buf ^ 1;
         a.logit = c->at<float>(L.logit[cur]); a.logit_prev = c->at<float>(L.logit[c->last_buf]);
         a.stat = c->at<float>(L.stat[cur]); a.stat_prev = c->at<float>(L.stat[c->last_buf]);
-        a.ticket = c->at<int32_t>(L.ticket); a.pending = c->pending ? 1 : 0;
+        a.ticket = c->at<int32_t>(L.ticket);
+        a.pending = c->pending ? 1 : 0;
         a.part_ml = c->at<float>(L.part_ml); a.part_o = c->at<float>(L.part_o);
         a.out = out;
         a.map = c->map();
@@ -618,6 +670,10 @@ int decode_step_impl(buzz_cache_t* c, const void* q, const void* k_new, const vo
         }
         // about 8 waves per compute unit; 4-wave blocks also where 8 waves' partial outputs would not fit the LDS
         a.waves = ((int64_t)L.units * a.n_splits <= cus && L.G * cfg.head_dim < kWideBlockMaxGD) ? 8 : 4;
+        // a unit's splits on one die, merged through that die's L2: possible when the units divide evenly over
+        // the 8 dies
+        a.xcd_local = (a.n_splits > 1 && L.units % 8 == 0 && !(cfg.flags & BUZZ_FLAG_DEVICE_MERGE) &&
+                       die_local_ok(&a.die_map)) ? 1 : 0;
         if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st,
                                              static_scratch ? Timing{} : prof_pair(c, 0)))
             return hip_rc(e);

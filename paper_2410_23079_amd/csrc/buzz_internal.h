@@ -90,6 +90,8 @@ struct AttnArgs {
     int32_t pending;     // 1: the previous step's score update has not been applied yet
     int32_t streaming;   // 1: K/V are read with the non-temporal hint (working set exceeds the last-level cache)
     int32_t fixed_tiles; // 1: waves take tiles in a fixed round-robin (bitwise reproducible results)
+    int32_t xcd_local;   // 1: blocks are renumbered so that a unit's splits share one die, and merge through its L2
+    uint32_t die_map;    // ... and the die (4 bits each) that serves launch-order block numbers 0..7 mod 8
     float scale_log2;    // softmax scale * log2(e)
 };
 

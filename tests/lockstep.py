@@ -15,7 +15,7 @@ import numpy as np
 import torch
 
 from oracle.buzz_oracle import OracleCache, OracleConfig
-from paper_2410_23079_amd import (FLAG_AUTO_EVICT, FLAG_CACHED, FLAG_DETERMINISTIC, FLAG_INTERVAL_NEW, FLAG_LOG_N,
+from paper_2410_23079_amd import (FLAG_AUTO_EVICT, FLAG_CACHED, FLAG_DETERMINISTIC, FLAG_DEVICE_MERGE, FLAG_INTERVAL_NEW, FLAG_LOG_N,
                                  FLAG_STREAMING, FLAG_THRESHOLD_TOTAL, BuzzCache, BuzzConfig)
 from workloads import Workload
 
@@ -56,10 +56,19 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
 
 
 def score_err(got: np.ndarray, ref: np.ndarray) -> float:
-    """max |got-ref| / max(1, |ref|); 0 for empty arrays."""
+    """max |got-ref| / max(1, |ref|) over the finite entries; 0 for empty arrays.  Where the reference is NaN or
+    infinite (planted starting scores stay that way: NaN + p = NaN, inf + p = inf) the other side must hold the
+    same, else the error is infinite."""
     if got.size == 0:
         return 0.0
-    return float((np.abs(got - ref) / np.maximum(1.0, np.abs(ref))).max())
+    fin = np.isfinite(ref)
+    odd_same = np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(got[~fin & ~np.isnan(ref)],
+                                                                                ref[~fin & ~np.isnan(ref)])
+    if not odd_same:
+        return float("inf")
+    if not fin.any():
+        return 0.0
+    return float((np.abs(got[fin] - ref[fin]) / np.maximum(1.0, np.abs(ref[fin]))).max())
 
 
 def gpu_prompt_scores(wl: Workload, prompt, n_obs: int, flags: int = 0):
@@ -77,9 +86,11 @@ def gpu_prompt_scores(wl: Workload, prompt, n_obs: int, flags: int = 0):
 
 def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=None, splits=0,
                  check_auto=True, capacity=0, log_n=False, threshold_total=None, deterministic=True,
-                 interval_new=False, kv_loads=None):
+                 interval_new=False, kv_loads=None, device_merge=False, plant=None):
     """Returns a dict of the worst errors seen; raises AssertionError on any parity failure.
-    kv_loads: None (the library decides), "streaming" or "cached" (forces the K/V load flavour)."""
+    kv_loads: None (the library decides), "streaming" or "cached" (forces the K/V load flavour).
+    device_merge: split partials always travel through device memory (else through one die's L2 where possible).
+    plant: callable that edits the fp32 prompt scores [B,Hkv,N] in place before both sides start from them."""
     G, D = wl.group, wl.head_dim
     N = prompt["K"].shape[2]
     steps = decode["q"].shape[0] if steps is None else steps
@@ -94,7 +105,8 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
         threshold_total = wl.threshold_total
     vflags = ((FLAG_LOG_N if log_n else 0) | (FLAG_THRESHOLD_TOTAL if threshold_total else 0)
               | (FLAG_DETERMINISTIC if deterministic else 0) | (FLAG_INTERVAL_NEW if interval_new else 0)
-              | {None: 0, "streaming": FLAG_STREAMING, "cached": FLAG_CACHED}[kv_loads])
+              | {None: 0, "streaming": FLAG_STREAMING, "cached": FLAG_CACHED}[kv_loads]
+              | (FLAG_DEVICE_MERGE if device_merge else 0))
     okw = dict(log_n=log_n, threshold_total=threshold_total, interval_new=interval_new)
 
     # ---- prompt scores: library vs oracle, then shared
@@ -108,6 +120,9 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
     err = score_err(got_ps, ref_ps)
     stats["prefill_score"] = err
     assert err <= SCORE_TOL, f"prefill scores off by {err}"
+    if plant is not None:
+        plant(ps)
+        got_ps = ps[uidx_b, uidx_h].double().cpu().numpy()
 
     # ---- both sides start from the same fp32 prompt scores
     gpu = BuzzCache(buzz_config(wl, flags=vflags, max_context=N + steps, capacity=capacity))
@@ -117,7 +132,7 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
     ora = OracleCache(oracle_config(wl, U, capacity=capacity, **okw))
     ora.prefill(Kp, Vp, init_score=got_ps[:, None, :])
     auto = None
-    if check_auto:
+    if check_auto and plant is None:                          # (the automatic cache scores its own prompt)
         auto = BuzzCache(buzz_config(wl, flags=FLAG_AUTO_EVICT | vflags, max_context=N + steps, capacity=capacity))
         if splits:
             auto.set_splits(splits)

@@ -43,7 +43,7 @@ def test_strerror_covers_all_codes():
 @pytest.mark.parametrize("bad", [
     dict(batch=0), dict(n_q_heads=7), dict(kv_dtype_code=5), dict(sink=-1), dict(window=-1), dict(segment=0),
     dict(keep=-1), dict(evict_every=0), dict(old_stride=-1), dict(max_context=0), dict(capacity=10),
-    dict(flags=256), dict(softmax_scale=float("nan")), dict(softmax_scale=-1.0),
+    dict(flags=512), dict(softmax_scale=float("nan")), dict(softmax_scale=-1.0),
 ])
 def test_invalid_configurations_are_rejected(bad):
     c = cfg()
