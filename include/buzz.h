@@ -63,14 +63,14 @@ enum {
     /* T bounds old + new tokens together instead of the new tokens alone: eviction fires when
        n_old + new_count reaches T.  This is how the proof of the Parameter Estimation theorem reads T; meant
        for old_stride > 1.  The old region then holds at most T rows, and a prefill keeps sampling until its
-       survivors fit T rows ("a container of length T + k + w", Remark 2) unless `capacity` says otherwise. */
+       survivors fit T rows (Remark 2 gives the size of that container) unless `capacity` says otherwise. */
     BUZZ_FLAG_THRESHOLD_TOTAL = 32u,
     /* Bitwise reproducible decode steps.  By default the waves of a decode block claim their next tile of
        cache rows from a shared counter, so which wave sums which rows depends on timing and the outputs and
        scores of two identical runs may differ in the last bits (always within the stated tolerances).  With
        this flag the assignment is fixed; measured cost: up to 5% of the step. */
     BUZZ_FLAG_DETERMINISTIC = 64u,
-    /* Ablation "no local max" (Sec. 4.4): new tokens are interval-sampled like old ones -- the first `keep`
+    /* Ablation "no local max" (Sec. 4.3): new tokens are interval-sampled like old ones -- the first `keep`
        rows of every segment survive whatever their scores.  (The other ablation of that section, swapped
        strides, needs no flag: segment = s^ and old_stride = s.) */
     BUZZ_FLAG_INTERVAL_NEW = 128u,
@@ -242,16 +242,6 @@ int buzz_cache_profile_read(buzz_cache_t* cache, buzz_profile_t* out);
  * Errors: BUZZ_EINVAL, BUZZ_EHIP.
  */
 int buzz_bench_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
-
-/*
- * Benchmark aid: how far the matrix and vector pipes of a SIMD overlap.  Every wave of `blocks` blocks of four
- * waves repeats, `iters` times, the instruction mix of one 16 x 64 tile of the matrix-core prompt scoring
- * (Sec. 3.2's attention probabilities summed per key): `work` 1 = its 16 MFMAs (16x16x32, fp16) only,
- * 2 = its 48 vector instructions (16 x fma, exp2, fma) only, 3 = both, the vector work on the MFMA results.
- * `out`: device buffer of blocks * 256 floats (written, content meaningless).  The caller times the launch.
- * Errors: BUZZ_EINVAL (work outside 1..3, blocks or iters < 1, blocks > 65535, NULL out), BUZZ_EHIP.
- */
-int buzz_bench_pipes(int32_t work, int32_t blocks, int32_t iters, float* out, void* hip_stream);
 
 /*
  * The eviction threshold the Parameter Estimation theorem (Sec. 3.4) recommends for stride s and window w

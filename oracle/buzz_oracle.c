@@ -43,7 +43,7 @@
  *     softmax scale by log(n)/log(512), n = number of tokens the query sees,
  *     itself included; and the threshold may instead bound old + new tokens
  *     together, which is how the proof of the Parameter Estimation theorem
- *     reads T; the ablation of Sec. 4.4 that drops the local-max function
+ *     reads T; the ablation of Sec. 4.3 that drops the local-max function
  *     keeps the first rows of every segment instead of the highest-scoring.
  */
 #include <math.h>
@@ -62,7 +62,7 @@ typedef struct {
     int32_t auto_evict;  /* decode_step evicts by itself when the count reaches T */
     int32_t variant;     /* bit 0: log-n scaled attention (Sec. 3.5): scale *= log(n)/log(512), n = tokens so far
                             bit 1: T bounds old + new tokens together (the reading used by the theorem's proof)
-                            bit 2: ablation "no local max" (Sec. 4.4): new tokens are interval-sampled too, i.e.
+                            bit 2: ablation "no local max" (Sec. 4.3): new tokens are interval-sampled too, i.e.
                                    the first `keep` rows of every segment survive whatever their scores */
     int64_t capacity;    /* logical row bound used by Remark 2; 0 => none */
     double  softmax_scale; /* 0 => 1/sqrt(head_dim) */

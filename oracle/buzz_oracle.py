@@ -95,7 +95,7 @@ class OracleConfig:
     softmax_scale: float = 0.0
     log_n: bool = False            # Sec. 3.5: scale *= log(n)/log(512)
     threshold_total: bool = False  # T bounds old + new tokens (theorem proof's reading)
-    interval_new: bool = False     # ablation (Sec. 4.4): new tokens interval-sampled, scores unused
+    interval_new: bool = False     # ablation (Sec. 4.3): new tokens interval-sampled, scores unused
 
 
 class OracleCache:

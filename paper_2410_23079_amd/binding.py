@@ -11,8 +11,7 @@ import os
 from dataclasses import dataclass
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# BUZZ_LIBRARY points at a differently built copy of the same library (tuning sweeps); default: the in-tree build
-_LIB_PATH = os.environ.get("BUZZ_LIBRARY") or os.path.join(_HERE, "libbuzz.so")
+_LIB_PATH = os.path.join(_HERE, "libbuzz.so")
 
 FLAG_AUTO_EVICT = 1
 FLAG_DRY_RUN = 2
@@ -28,7 +27,7 @@ DTYPE_CODES = {"fp32": 0, "fp16": 1, "bf16": 2}
 EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step",
            "buzz_decode_step_static", "buzz_evict",
            "buzz_cache_destroy", "buzz_cache_len", "buzz_cache_export", "buzz_cache_set_splits", "buzz_cache_profile",
-           "buzz_cache_profile_read", "buzz_bench_copy", "buzz_bench_pipes", "buzz_suggest_threshold", "buzz_strerror"]
+           "buzz_cache_profile_read", "buzz_bench_copy", "buzz_suggest_threshold", "buzz_strerror"]
 
 
 class BuzzError(RuntimeError):
@@ -108,7 +107,6 @@ def load_library():
     lib.buzz_cache_profile.argtypes = [P, ctypes.c_int]
     lib.buzz_cache_profile_read.argtypes = [P, ctypes.POINTER(_Profile)]
     lib.buzz_bench_copy.argtypes = [P, P, ctypes.c_size_t, P]
-    lib.buzz_bench_pipes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, P, P]
     lib.buzz_suggest_threshold.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.buzz_suggest_threshold.restype = ctypes.c_int64
     lib.buzz_strerror.argtypes = [ctypes.c_int]
@@ -138,13 +136,6 @@ def bench_copy(dst, src, stream=None):
     """Plain device copy of ``src`` into ``dst`` (same byte size) with the library's own copy kernel."""
     nbytes = src.numel() * src.element_size()
     _check(load_library().buzz_bench_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)), "buzz_bench_copy")
-
-
-def bench_pipes(work: int, blocks: int, iters: int, out, stream=None):
-    """Launch the matrix / vector pipe overlap probe (``work`` 1 MFMAs, 2 vector work, 3 both); ``out``: float32
-    device tensor of at least ``blocks * 256`` elements."""
-    assert out.numel() >= blocks * 256
-    _check(load_library().buzz_bench_pipes(work, blocks, iters, out.data_ptr(), _stream(stream)), "buzz_bench_pipes")
 
 
 def _ptr(t):

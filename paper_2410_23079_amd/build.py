@@ -24,16 +24,13 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra_flags=(), out_path: str = LIB, obj_dir: str = CSRC) -> str:
-    """Compile every source and link the shared library; always recompiles.
-
-    ``extra_flags`` / ``out_path`` / ``obj_dir`` let a tuning sweep build differently configured copies elsewhere."""
+def build(verbose: bool = False) -> str:
+    """Compile every source and link the shared library; always recompiles."""
     objs = []
     procs = []
-    os.makedirs(obj_dir, exist_ok=True)
     for src, stem, defs in SOURCES:
-        obj = os.path.join(obj_dir, stem + ".o")
-        cmd = ["hipcc", "-x", "hip", *FLAGS, *defs, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+        obj = os.path.join(CSRC, stem + ".o")
+        cmd = ["hipcc", "-x", "hip", *FLAGS, *defs, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
                "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -49,9 +46,9 @@ def build(verbose: bool = False, extra_flags=(), out_path: str = LIB, obj_dir: s
         failed |= p.returncode != 0
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out_path, *objs]
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
-    return out_path
+    return LIB
 
 
 if __name__ == "__main__":

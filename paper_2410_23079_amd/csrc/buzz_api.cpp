@@ -761,12 +761,6 @@ int buzz_bench_copy(void* dst, const void* src, size_t bytes, void* hip_stream)
     return hip_rc(launch_plain_copy(dst, src, bytes, (hipStream_t)hip_stream));
 }
 
-int buzz_bench_pipes(int32_t work, int32_t blocks, int32_t iters, float* out, void* hip_stream)
-{
-    if (work < 1 || work > 3 || blocks < 1 || blocks > 65535 || iters < 1 || !out) return BUZZ_EINVAL;
-    return hip_rc(launch_pipe_probe(work, blocks, iters, out, (hipStream_t)hip_stream));
-}
-
 int64_t buzz_suggest_threshold(int32_t segment, int32_t window)
 {
     if (segment < 1 || window < 0) return 0;

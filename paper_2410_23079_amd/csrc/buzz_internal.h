@@ -183,7 +183,6 @@ hipError_t launch_gather_rows(const GatherArgs& a, int units, hipStream_t st, Ti
 hipError_t launch_fill_f32(float* dst, const float* src, int64_t n, hipStream_t st);  // src NULL => zeros
 hipError_t launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_evict_new_rows(const EvictArgs& a, int units, hipStream_t st, Timing tm = {});
-hipError_t launch_pipe_probe(int work, int blocks, int iters, float* out, hipStream_t st);
 hipError_t launch_obs_scores(int dtype, int D, int G, const ObsArgs& a, int units, hipStream_t st, Timing tm = {});
 int obs_pass_queries(int dtype, int G);   // queries of one head a single scoring pass covers
 int attn_tile_rows(int dtype, int D, int G);   // rows one block consumes per loop trip (split sizes are multiples)

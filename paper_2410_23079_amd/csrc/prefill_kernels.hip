@@ -522,43 +522,6 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
     }
 }
 
-// Benchmark aid: the instruction mix of one 16 x 64 tile of the column-sum step with nothing else around it --
-// four chains of four MFMAs (WORK & 1) and, per product, fma, exp2, fma (WORK & 2; on the MFMA results when
-// both run) -- repeated `iters` times by every wave.  Timing it with 1, 2 and 3 says how far the matrix and
-// vector pipes of a SIMD overlap.
-template <int WORK>
-__global__ __launch_bounds__(256) void pipe_probe_kernel(float* out, int iters, float s)
-{
-    f16x8_t a[4], b[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { a[c][i] = (_Float16)(threadIdx.x * 0.001f + i + c); b[c][i] = (_Float16)(0.01f * (i + c)); }
-    float col[4] = {0.f, 0.f, 0.f, 0.f};
-    f32x4 keep = {0.f, 0.f, 0.f, 0.f};
-    float x = threadIdx.x * 1e-3f;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            f32x4 r = {x + c, x * 1.5f + c, x * 2.5f - c, x * 3.5f + 2 * c};
-            if (WORK & 1) {
-                r = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int p = 0; p < 4; ++p) r = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[p], b[c], r, 0, 0, 0);
-            }
-            if (WORK & 2) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) col[c] = fmaf(__builtin_amdgcn_exp2f(fmaf(r[v], s, -1.0f)), 0.5f, col[c]);
-            } else {
-                keep += r;
-            }
-        }
-        x += 1e-6f;
-        a[0][0] += (_Float16)0.001f;
-    }
-    out[blockIdx.x * 256 + threadIdx.x] = col[0] + col[1] + col[2] + col[3] + keep[0] + keep[1] + keep[2] + keep[3];
-}
-
 template <int DT, int D>
 hipError_t launch_obs_mfma_t(const ObsArgs& a, int units, hipStream_t st, Timing tm)
 {
@@ -611,13 +574,6 @@ int obs_pass_queries(int dtype, int G)
     return dtype == BUZZ_FP32 ? kObsRows / G : kObsPassRows;
 }
 
-hipError_t launch_pipe_probe(int work, int blocks, int iters, float* out, hipStream_t st)
-{
-    if (work == 1) hipLaunchKernelGGL(pipe_probe_kernel<1>, dim3(blocks), dim3(256), 0, st, out, iters, 0.001f);
-    else if (work == 2) hipLaunchKernelGGL(pipe_probe_kernel<2>, dim3(blocks), dim3(256), 0, st, out, iters, 0.001f);
-    else hipLaunchKernelGGL(pipe_probe_kernel<3>, dim3(blocks), dim3(256), 0, st, out, iters, 0.001f);
-    return hipGetLastError();
-}
 
 hipError_t launch_obs_scores(int dtype, int D, int /*G*/, const ObsArgs& a, int units, hipStream_t st, Timing tm)
 {

@@ -319,7 +319,7 @@ def test_threshold_bounds_old_plus_new_with_theorem_parameters():
 
 
 def test_interval_sampling_of_new_tokens():
-    """Ablation of Sec. 4.4 without the local-max function."""
+    """Ablation of Sec. 4.3 without the local-max function."""
     run(small(prompt=300, decode_steps=48, keep=2), interval_new=True)
 
 
@@ -359,7 +359,7 @@ def test_objective_on_clustered_keys():
 def test_local_max_beats_the_ablations_on_the_papers_objective():
     """Sec. 3.1 states the goal as keeping the evicted cache's attention output close to the full one.
     On synthetic keys with planted heavy hitters, at one cache budget, BUZZ's output must be closer to full
-    attention than the no-local-max ablation and than sink + window alone (Sec. 4.4 reports the same
+    attention than the no-local-max ablation and than sink + window alone (Sec. 4.3 reports the same
     ordering in ROUGE, which needs the trained model and is not reproduced here)."""
     import math
     from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_INTERVAL_NEW, BuzzCache
@@ -392,7 +392,7 @@ def test_local_max_beats_the_ablations_on_the_papers_objective():
     buzz, n_buzz = deviation()
     no_max, n_no_max = deviation(FLAG_INTERVAL_NEW)
     window_only, n_window = deviation(keep=0)
-    swapped, n_swapped = deviation(segment=(wl.segment + 1) // 2, old_stride=wl.segment)   # Sec. 4.4, first ablation
+    swapped, n_swapped = deviation(segment=(wl.segment + 1) // 2, old_stride=wl.segment)   # Sec. 4.3, first ablation
     print(f"[objective] mean |O^ - O| / |O|: BUZZ {buzz:.4f} ({n_buzz} rows)  no local max {no_max:.4f} ({n_no_max})  "
           f"sink+window {window_only:.4f} ({n_window})  swapped strides {swapped:.4f} ({n_swapped})", flush=True)
     assert n_buzz == n_no_max

@@ -479,7 +479,7 @@ def test_total_threshold_runs_the_proofs_recurrence_by_itself(s):
 
 
 def test_interval_sampling_of_new_tokens_ignores_scores():
-    """Ablation without the local-max function (Sec. 4.4): survivors are fixed positions, whatever the scores."""
+    """Ablation without the local-max function (Sec. 4.3): survivors are fixed positions, whatever the scores."""
     k, w, s, c, T, D = 2, 5, 4, 1, 11, 2
     r = np.random.default_rng(31)
     N = k + w + 2 * T + 3
