@@ -78,7 +78,13 @@ enum {
        over the GPU's 8 dies, the blocks of a pair are placed on one die and exchange their partial results
        through that die's L2.  With this flag they always exchange them through device memory instead (the
        path taken anyway for other shapes).  Results are the same; meant for comparison. */
-    BUZZ_FLAG_DEVICE_MERGE = 256u
+    BUZZ_FLAG_DEVICE_MERGE = 256u,
+    /* H2O-style baseline (Sec. 4.1: greedy selection by accumulated attention score, no segmentation): at every
+       eviction ALL rows between sink and window, old and new alike, form one segment of which the `keep`
+       highest-scoring rows survive (ties to the lowest index), so the cache holds sink + keep + window rows plus
+       up to T buffered ones.  `segment` and `old_stride` are ignored.  Not combinable with THRESHOLD_TOTAL or
+       INTERVAL_NEW. */
+    BUZZ_FLAG_GLOBAL_TOPK = 512u
 };
 
 /* Symbols follow the paper's notation table (Sec. 3.3). */
@@ -90,7 +96,7 @@ typedef struct buzz_config {
     int32_t kv_dtype;     /* BUZZ_FP32 / BUZZ_FP16 / BUZZ_BF16 */
     int32_t sink;         /* k : first tokens always kept ("attention sink") */
     int32_t window;       /* w : most recent tokens always kept ("sliding window") */
-    int32_t segment;      /* s : stride of the segments ("hives") for new tokens; 1..4096 */
+    int32_t segment;      /* s : stride of the segments ("hives") for new tokens; >= 1 */
     int32_t keep;         /* rows kept per segment; the paper keeps 1; 0 keeps none (sink + window only) */
     int32_t evict_every;  /* T : number of tokens buffered outside the window before one eviction */
     int32_t old_stride;   /* s^: interval-sampling stride for old tokens; 0 => floor((s+1)/2) as in the paper,

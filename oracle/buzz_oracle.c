@@ -44,7 +44,10 @@
  *     itself included; and the threshold may instead bound old + new tokens
  *     together, which is how the proof of the Parameter Estimation theorem
  *     reads T; the ablation of Sec. 4.3 that drops the local-max function
- *     keeps the first rows of every segment instead of the highest-scoring.
+ *     keeps the first rows of every segment instead of the highest-scoring;
+ *     the H2O-style baseline the paper compares with (Sec. 4.1) keeps the
+ *     `keep` highest accumulated scores among all rows between sink and
+ *     window, with no segments and no old / new distinction.
  */
 #include <math.h>
 #include <stdint.h>
@@ -63,7 +66,10 @@ typedef struct {
     int32_t variant;     /* bit 0: log-n scaled attention (Sec. 3.5): scale *= log(n)/log(512), n = tokens so far
                             bit 1: T bounds old + new tokens together (the reading used by the theorem's proof)
                             bit 2: ablation "no local max" (Sec. 4.3): new tokens are interval-sampled too, i.e.
-                                   the first `keep` rows of every segment survive whatever their scores */
+                                   the first `keep` rows of every segment survive whatever their scores
+                            bit 3: H2O-style baseline (Sec. 4.1, "greedy accumulated attention scores"): every row
+                                   between sink and window, old or new, competes in one segment; the `keep`
+                                   highest-scoring survive */
     int64_t capacity;    /* logical row bound used by Remark 2; 0 => none */
     double  softmax_scale; /* 0 => 1/sqrt(head_dim) */
 } oracle_config;
@@ -159,12 +165,14 @@ static int ranks_before(double sa, int64_t ia, double sb, int64_t ib)
 /* The eviction branch of Alg. 1 (split, sample both parts, concatenate) plus Alg. 2, on one unit. */
 static int unit_evict(const oracle_config *c, unit_t *x)
 {
-    const int64_t k = c->sink, w = c->window, s = c->segment, D = c->head_dim;
+    const int64_t k = c->sink, w = c->window, D = c->head_dim;
     const int64_t sh = old_stride_of(c);
     if (x->n <= k + w) return 0;                     /* Remark 1: fill sink and window first */
-    const int64_t lo = k + x->n_old;                 /* K_new = K[k + n_old : -w]  (Alg. 1) */
+    const int global = c->variant & 8;               /* H2O-style baseline: no old / new split, no segments */
+    const int64_t lo = global ? k : k + x->n_old;    /* K_new = K[k + n_old : -w]  (Alg. 1) */
     const int64_t hi = x->n - w;
     if (lo > hi) return ORACLE_EINVAL;
+    const int64_t s = global ? (hi > lo ? hi - lo : 1) : c->segment;   /* ... = one segment over the whole middle */
 
     int64_t *keep_idx = malloc(sizeof(int64_t) * (size_t)(x->n + 1));
     if (!keep_idx) return ORACLE_ENOMEM;

@@ -96,6 +96,7 @@ class OracleConfig:
     log_n: bool = False            # Sec. 3.5: scale *= log(n)/log(512)
     threshold_total: bool = False  # T bounds old + new tokens (theorem proof's reading)
     interval_new: bool = False     # ablation (Sec. 4.3): new tokens interval-sampled, scores unused
+    global_topk: bool = False      # H2O-style baseline (Sec. 4.1): top `keep` of all rows between sink and window
 
 
 class OracleCache:
@@ -106,7 +107,8 @@ class OracleCache:
         self._lib = _load()
         c = _Cfg(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.sink, cfg.window,
                  cfg.segment, cfg.keep, cfg.evict_every, cfg.old_stride, int(cfg.auto_evict),
-                 int(cfg.log_n) | (int(cfg.threshold_total) << 1) | (int(cfg.interval_new) << 2),
+                 int(cfg.log_n) | (int(cfg.threshold_total) << 1) | (int(cfg.interval_new) << 2)
+                 | (int(cfg.global_topk) << 3),
                  cfg.capacity, cfg.softmax_scale)
         h = ctypes.c_void_p()
         _chk(self._lib.oracle_create(ctypes.byref(c), ctypes.byref(h)), "oracle_create")

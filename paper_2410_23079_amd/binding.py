@@ -22,6 +22,7 @@ FLAG_THRESHOLD_TOTAL = 32
 FLAG_DETERMINISTIC = 64
 FLAG_INTERVAL_NEW = 128
 FLAG_DEVICE_MERGE = 256
+FLAG_GLOBAL_TOPK = 512
 DTYPE_CODES = {"fp32": 0, "fp16": 1, "bf16": 2}
 
 EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step",

@@ -108,22 +108,27 @@ int make_layout(const buzz_config_t* c, Layout* L)
     if (c->old_stride < 0 || c->max_context < 1 || c->capacity < 0 || c->reserved != 0) return BUZZ_EINVAL;
     if (c->flags & ~(uint32_t)(BUZZ_FLAG_AUTO_EVICT | BUZZ_FLAG_DRY_RUN | BUZZ_FLAG_STREAMING | BUZZ_FLAG_CACHED |
                               BUZZ_FLAG_LOG_N | BUZZ_FLAG_THRESHOLD_TOTAL | BUZZ_FLAG_DETERMINISTIC |
-                              BUZZ_FLAG_INTERVAL_NEW | BUZZ_FLAG_DEVICE_MERGE))
+                              BUZZ_FLAG_INTERVAL_NEW | BUZZ_FLAG_DEVICE_MERGE | BUZZ_FLAG_GLOBAL_TOPK))
         return BUZZ_EINVAL;
     if ((c->flags & BUZZ_FLAG_STREAMING) && (c->flags & BUZZ_FLAG_CACHED)) return BUZZ_EINVAL;
+    if ((c->flags & BUZZ_FLAG_GLOBAL_TOPK) && (c->flags & (BUZZ_FLAG_THRESHOLD_TOTAL | BUZZ_FLAG_INTERVAL_NEW))) return BUZZ_EINVAL;
     if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BUZZ_EINVAL;
     const int G = c->n_q_heads / c->n_kv_heads;
     if (!attn_supported(c->kv_dtype, c->head_dim, G)) return BUZZ_EUNSUPPORTED;
-    if (c->segment > kMaxSegment) return BUZZ_EUNSUPPORTED;
+    if (c->segment > (1 << 28)) return BUZZ_EUNSUPPORTED;
     const int64_t units = (int64_t)c->batch * c->n_kv_heads;
     if (units > 65535) return BUZZ_EUNSUPPORTED;
     if (c->max_context > (1 << 28)) return BUZZ_EUNSUPPORTED;
 
     const int64_t k = c->sink, w = c->window, s = c->segment, T = c->evict_every;
-    const int64_t keep = c->keep < c->segment ? c->keep : c->segment;   // a segment cannot yield more rows than it has
+    const bool global = c->flags & BUZZ_FLAG_GLOBAL_TOPK;       // one segment over everything between sink and window
+    const int64_t keep = (global || c->keep < c->segment) ? c->keep : c->segment;   // a segment cannot yield more rows than it has
     const int64_t M = c->max_context > k + w ? c->max_context - k - w : 0;   // tokens that can ever be "new"
     int64_t old_cap;
-    if (c->capacity > 0) {
+    if (global) {
+        old_cap = keep < M ? keep : M;                          // the survivors of the one segment
+        if (c->capacity > 0 && c->capacity < k + old_cap + w + T) return BUZZ_EINVAL;
+    } else if (c->capacity > 0) {
         old_cap = c->capacity - k - w - T;
         if (old_cap < 0) return BUZZ_EINVAL;
     } else if (c->flags & BUZZ_FLAG_THRESHOLD_TOTAL) {
@@ -156,6 +161,10 @@ int make_layout(const buzz_config_t* c, Layout* L)
     const int64_t sel_bound = keep * (ceil_div(M, s) + 1);
     L->sel_stride = (int32_t)(keep == 0 ? 1 : (sel_bound < M ? sel_bound : (M > 0 ? M : 1)));
     L->st_rows = L->old_stride > 1 ? (int32_t)ceil_div(old_cap, L->old_stride) + 1 : 0;
+    if (global) {                                               // survivors pass through the staging rows
+        L->sel_stride = (int32_t)(old_cap > 0 ? old_cap : 1);
+        L->st_rows = (int32_t)old_cap;
+    }
 
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
@@ -305,6 +314,11 @@ bool evict_sizes(const buzz_cache_t* c, int64_t n, int64_t n_old, EvictSizes* z)
     if (n <= k + w) return false;
     const int64_t newc = n - k - n_old - w > 0 ? n - k - n_old - w : 0;
     z->newc = newc;
+    if (c->cfg.flags & BUZZ_FLAG_GLOBAL_TOPK) {                // old and new rows are one segment
+        z->old2 = 0;
+        z->new2 = keep < n - k - w ? keep : n - k - w;
+        return true;
+    }
     z->old2 = ceil_div(n_old, c->L.old_stride);                // interval sampling keeps offsets 0, s^, 2 s^, ...
     z->new2 = keep * (newc / s) + (newc % s < keep ? newc % s : keep);   // every segment yields min(keep, len)
     return true;
@@ -337,6 +351,39 @@ int evict_impl(buzz_cache_t* c, hipStream_t st)
     if (!evict_sizes(c, c->n(), c->n_old, &z)) return BUZZ_OK; // Remark 1
     const int64_t newc = z.newc, sh = L.old_stride, old2 = z.old2, new2 = z.new2;
     if (old2 + new2 > L.old_cap) return BUZZ_ECAPACITY;
+    if (cfg.flags & BUZZ_FLAG_GLOBAL_TOPK) {
+        // H2O-style: the top `keep` of ALL rows between sink and window survive.  Survivors may sit anywhere in
+        // the old region or the ring and land where old rows are, so they travel through the staging rows.
+        if (int rc = flush_scores(c, st)) return rc;
+        if (!c->dry && new2 > 0) {
+            if (c->prof) c->prof_evictions += 1;
+            const int64_t mid = c->n() - k - cfg.window;
+            SelectArgs sa{};
+            sa.score = c->at<float>(L.score); sa.unit_stride = L.cap;
+            sa.map = c->map(); sa.lo = (int32_t)k; sa.new_count = (int32_t)mid;
+            sa.segment = (int32_t)(mid > kMaxWaveSegment ? mid : kMaxWaveSegment);   // one segment, whatever its length
+            sa.keep = L.keep; sa.ignore_scores = 0;
+            sa.sel = c->at<int32_t>(L.sel); sa.sel_stride = L.sel_stride;
+            if (hipError_t e = launch_segment_topk(sa, L.units, st, prof_pair(c, 2))) return hip_rc(e);
+            GatherArgs g = cache_gather_base(c);
+            g.src_map = c->map();
+            g.sel = c->at<int32_t>(L.sel); g.sel_stride = L.sel_stride; g.sel_start = 0; g.sel_step = 1;
+            g.dstK = c->at<char>(L.stK); g.dstV = c->at<char>(L.stV);
+            g.dstScore = c->at<float>(L.stScore); g.dstPos = c->at<int32_t>(L.stPos);
+            g.dst_unit_rows = L.st_rows; g.dst_start = 0; g.n_rows = (int32_t)new2;
+            if (hipError_t e = launch_gather_rows(g, L.units, st, prof_pair(c, 2))) return hip_rc(e);
+            GatherArgs b = cache_gather_base(c);
+            b.srcK = c->at<char>(L.stK); b.srcV = c->at<char>(L.stV);
+            b.srcScore = c->at<float>(L.stScore); b.srcPos = c->at<int32_t>(L.stPos);
+            b.src_unit_rows = L.st_rows; b.src_start = 0; b.src_step = 1;
+            b.dst_start = (int32_t)k; b.n_rows = (int32_t)new2;
+            if (hipError_t e = launch_gather_rows(b, L.units, st, prof_pair(c, 2))) return hip_rc(e);
+        }
+        c->n_old = new2;
+        c->head = (c->head + newc) % L.ring_cap;
+        c->tail -= newc;
+        return BUZZ_OK;
+    }
     // Old rows that stay where they are (old stride 1) leave only the new rows to deal with, and one launch
     // does that: a score update still pending stays pending for every row that keeps its place.
     const bool in_place = old2 == c->n_old && (s + keep) * (int64_t)(4 * sizeof(float)) <= 65536;
@@ -484,7 +531,10 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
     const int64_t M = N - k - w;                                // prompt tokens between sink and window
     const bool sample = M >= T;
     int64_t survivors = 0, sel_step = 1;
-    if (sample) {
+    const bool global = cfg.flags & BUZZ_FLAG_GLOBAL_TOPK;
+    if (sample && global) {
+        survivors = keep < M ? keep : M;                        // H2O-style: one segment over the whole middle
+    } else if (sample) {
         const int64_t last = M % s < keep ? M % s : keep;
         survivors = keep * (M / s) + last;
         if (L.old_stride > 1 && (cfg.capacity > 0 || (cfg.flags & BUZZ_FLAG_THRESHOLD_TOTAL))) {   // Remark 2: sample until it fits
@@ -544,7 +594,8 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
                 sa.score = ps; sa.unit_stride = N;
                 sa.map = RingMap{0, 0, 0, 0};
                 sa.lo = (int32_t)k; sa.new_count = (int32_t)M;
-                sa.segment = cfg.segment; sa.keep = L.keep;
+                sa.segment = global ? (int32_t)(M > kMaxWaveSegment ? M : kMaxWaveSegment) : cfg.segment;
+                sa.keep = L.keep;
                 sa.ignore_scores = (cfg.flags & BUZZ_FLAG_INTERVAL_NEW) ? 1 : 0;
                 sa.sel = c->at<int32_t>(L.sel); sa.sel_stride = L.sel_stride;
                 if (hipError_t e = launch_segment_topk(sa, L.units, st)) return hip_rc(e);

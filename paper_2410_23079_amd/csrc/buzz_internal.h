@@ -24,7 +24,7 @@ namespace buzz {
 constexpr int kMaxSplits = 128;        // upper bound on key-range splits per unit
 constexpr int kDefaultCUs = 256;       // MI355X; replaced by the device's own count at the first launch
 constexpr int kMaxBlocks = 4096;       // partial buffers are sized for units * splits <= this (or 1 split per unit)
-constexpr int kMaxSegment = 4096;
+constexpr int kMaxWaveSegment = 4096;  // longest segment the one-wave-per-segment selection kernels rank (LDS slice)
 constexpr int kMinSplitRows = 128;     // automatic split policy: no split shorter than this
 constexpr int kStageFloats = 4096;     // LDS logit staging of one split that every shape can have
 constexpr int kStageFloatsMax = 8192;  // ... and what a shape gets when the block's other LDS arrays leave room

@@ -54,6 +54,95 @@ __global__ __launch_bounds__(256) void segment_topk_kernel(const SelectArgs a)
     }
 }
 
+// Segments too long for one wave's slice of the LDS (and the single segment of the H2O-style variant, which
+// spans every row between sink and window): one block per (segment, unit) finds the `take` largest scores by a
+// radix select on the order-preserving integer image of the scores -- four passes of a 256-bin histogram in
+// LDS, most significant byte first, each narrowing the candidates to one bin -- which ends with the key of the
+// last survivor and the number of rows with exactly that key that still fit.  A final pass in index order keeps
+// every row with a larger key and the first of the equal ones (ties go to the lowest index), and numbers the
+// survivors with a block-wide prefix sum so that they come out in index order.  Same result as the wave kernel.
+constexpr int kTopkBlock = 1024;
+
+__device__ inline unsigned score_key(float v)      // larger score <=> larger key; NaN ranks with -inf; -0 == +0
+{
+    if (v != v) v = -INFINITY;
+    const unsigned b = __float_as_uint(v + 0.0f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// exclusive prefix count of `flag` over the block in thread order, and the block total (both via LDS `tmp`,
+// one slot per wave plus one); every thread of the block must call it
+__device__ inline int block_prefix(bool flag, int* tmp, int& total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const unsigned long long m = __ballot(flag);
+    if (lane == 0) tmp[wave] = __popcll(m);
+    __syncthreads();
+    int before = 0, sum = 0;
+    for (int w = 0; w < nw; ++w) { const int c = tmp[w]; before += w < wave ? c : 0; sum += c; }
+    __syncthreads();                               // tmp is reused by the next call
+    total = sum;
+    return before + __popcll(m & ((1ull << lane) - 1ull));
+}
+
+__global__ __launch_bounds__(kTopkBlock) void segment_topk_block_kernel(const SelectArgs a)
+{
+    __shared__ int hist[256];
+    __shared__ int tmp[kTopkBlock / 64];
+    __shared__ unsigned sh_prefix;
+    __shared__ int sh_remaining;
+    const int tid = threadIdx.x, seg = blockIdx.x, unit = blockIdx.y;
+    const long long start = (long long)seg * a.segment;
+    const int len = (int)min((long long)a.segment, (long long)a.new_count - start);
+    const int take = min(a.keep, len);
+    if (take <= 0) return;
+    const float* base = a.score + (size_t)unit * a.unit_stride;
+    auto key_of = [&](int e) {
+        const int row = a.lo + (int)start + e;
+        return a.ignore_scores ? 0x80000000u : score_key(base[a.map.ring_cap ? a.map.phys(row) : row]);
+    };
+    // radix select: after the pass for byte b, `prefix` holds the top bytes of the last survivor's key and
+    // `remaining` how many rows are still to be taken among those that share them
+    unsigned prefix = 0, mask = 0;
+    int remaining = take;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int e = tid; e < len; e += kTopkBlock) {
+            const unsigned k = key_of(e);
+            if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int left = remaining, bin = 255;
+            for (; bin > 0; --bin) {               // from the largest digit down: the bin where the count runs out
+                if (hist[bin] >= left) break;
+                left -= hist[bin];
+            }
+            sh_prefix = prefix | ((unsigned)bin << shift);
+            sh_remaining = left;
+        }
+        __syncthreads();
+        prefix = sh_prefix; remaining = sh_remaining;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    // prefix = key of the last survivor; `remaining` (>= 1) rows with that key survive, the lowest indices first
+    int ties_seen = 0, kept_seen = 0;
+    int* out = a.sel + (size_t)unit * a.sel_stride + (size_t)seg * a.keep;
+    for (int e0 = 0; e0 < len; e0 += kTopkBlock) {
+        const int e = e0 + tid;
+        const unsigned k = e < len ? key_of(e) : 0u;
+        const bool eq = e < len && k == prefix, gt = e < len && k > prefix;
+        int n_eq, n_kp;
+        const int eq_before = ties_seen + block_prefix(eq, tmp, n_eq);
+        const bool kp = gt || (eq && eq_before < remaining);
+        const int pos = kept_seen + block_prefix(kp, tmp, n_kp);
+        if (kp) out[pos] = a.lo + (int)start + e;
+        ties_seen += n_eq; kept_seen += n_kp;
+    }
+}
+
 // Eviction of the new rows in one launch, for caches whose old rows stay in place.  A wave ranks one segment
 // as above and then moves the segment's survivors itself (their destination depends on nothing but the
 // segment number and the rank).  A score update that the last decode step left pending is applied on the fly
@@ -194,6 +283,11 @@ hipError_t launch_segment_topk(const SelectArgs& a, int units, hipStream_t st, T
 {
     const int n_seg = (a.new_count + a.segment - 1) / a.segment;
     if (n_seg <= 0) return hipSuccess;
+    if (a.segment > kMaxWaveSegment) {             // a segment's scores no longer fit a wave's slice of the LDS
+        if (n_seg > 65535) return hipErrorInvalidValue;
+        BUZZ_LAUNCH(segment_topk_block_kernel, dim3(n_seg, units), dim3(kTopkBlock), 0, st, tm, a);
+        return hipGetLastError();
+    }
     dim3 grid((n_seg + kSelWaves - 1) / kSelWaves, units), block(256);
     const size_t lds = (size_t)kSelWaves * a.segment * sizeof(float);
     BUZZ_LAUNCH(segment_topk_kernel, grid, block, lds, st, tm, a);

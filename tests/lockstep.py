@@ -15,7 +15,7 @@ import numpy as np
 import torch
 
 from oracle.buzz_oracle import OracleCache, OracleConfig
-from paper_2410_23079_amd import (FLAG_AUTO_EVICT, FLAG_CACHED, FLAG_DETERMINISTIC, FLAG_DEVICE_MERGE, FLAG_INTERVAL_NEW, FLAG_LOG_N,
+from paper_2410_23079_amd import (FLAG_AUTO_EVICT, FLAG_CACHED, FLAG_DETERMINISTIC, FLAG_DEVICE_MERGE, FLAG_GLOBAL_TOPK, FLAG_INTERVAL_NEW, FLAG_LOG_N,
                                  FLAG_STREAMING, FLAG_THRESHOLD_TOTAL, BuzzCache, BuzzConfig)
 from workloads import Workload
 
@@ -86,7 +86,7 @@ def gpu_prompt_scores(wl: Workload, prompt, n_obs: int, flags: int = 0):
 
 def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=None, splits=0,
                  check_auto=True, capacity=0, log_n=False, threshold_total=None, deterministic=True,
-                 interval_new=False, kv_loads=None, device_merge=False, plant=None):
+                 interval_new=False, kv_loads=None, device_merge=False, plant=None, global_topk=False):
     """Returns a dict of the worst errors seen; raises AssertionError on any parity failure.
     kv_loads: None (the library decides), "streaming" or "cached" (forces the K/V load flavour).
     device_merge: split partials always travel through device memory (else through one die's L2 where possible).
@@ -106,8 +106,8 @@ def run_lockstep(wl: Workload, prompt, decode, units=None, steps=None, n_obs=Non
     vflags = ((FLAG_LOG_N if log_n else 0) | (FLAG_THRESHOLD_TOTAL if threshold_total else 0)
               | (FLAG_DETERMINISTIC if deterministic else 0) | (FLAG_INTERVAL_NEW if interval_new else 0)
               | {None: 0, "streaming": FLAG_STREAMING, "cached": FLAG_CACHED}[kv_loads]
-              | (FLAG_DEVICE_MERGE if device_merge else 0))
-    okw = dict(log_n=log_n, threshold_total=threshold_total, interval_new=interval_new)
+              | (FLAG_DEVICE_MERGE if device_merge else 0) | (FLAG_GLOBAL_TOPK if global_topk else 0))
+    okw = dict(log_n=log_n, threshold_total=threshold_total, interval_new=interval_new, global_topk=global_topk)
 
     # ---- prompt scores: library vs oracle, then shared
     Kp, Vp = unit_slices(prompt["K"], units, 1), unit_slices(prompt["V"], units, 1)

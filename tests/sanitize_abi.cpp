@@ -79,8 +79,10 @@ int main()
     buzz_config_t bad = config(4, 64, 16, 1, 16, 1, 0, 1000, 0);
     bad.n_q_heads = 7;
     if (buzz_workspace_bytes(&bad, &bytes) != BUZZ_EINVAL) rc |= fail("bad heads accepted", 0, 0);
-    bad = config(4, 64, 5000, 1, 16, 1, 0, 1000, 0);
-    if (buzz_workspace_bytes(&bad, &bytes) != BUZZ_EUNSUPPORTED) rc |= fail("long segment accepted", 0, 0);
+    bad = config(4, 64, 16, 1, 16, 1, 0, 1000, 0);
+    bad.head_dim = 96;
+    if (buzz_workspace_bytes(&bad, &bytes) != BUZZ_EUNSUPPORTED) rc |= fail("head_dim without a kernel accepted", 0, 0);
+    rc |= drive(4, 64, 5000, 3, 6000, 1, 12000, 40);           // a segment beyond one wave's reach, ragged
     // an eviction that cannot fit an explicit capacity is refused before the step changes anything
     buzz_config_t tight = config(2, 10, 4, 1, 4, 1, BUZZ_FLAG_AUTO_EVICT, 1000, 2 + 10 + 4 + 6);
     buzz_cache_t* h = nullptr;

@@ -43,7 +43,7 @@ def test_strerror_covers_all_codes():
 @pytest.mark.parametrize("bad", [
     dict(batch=0), dict(n_q_heads=7), dict(kv_dtype_code=5), dict(sink=-1), dict(window=-1), dict(segment=0),
     dict(keep=-1), dict(evict_every=0), dict(old_stride=-1), dict(max_context=0), dict(capacity=10),
-    dict(flags=512), dict(softmax_scale=float("nan")), dict(softmax_scale=-1.0),
+    dict(flags=1024), dict(flags=512 | 32), dict(flags=512 | 128), dict(softmax_scale=float("nan")), dict(softmax_scale=-1.0),
 ])
 def test_invalid_configurations_are_rejected(bad):
     c = cfg()
@@ -54,7 +54,7 @@ def test_invalid_configurations_are_rejected(bad):
     assert load_library().buzz_workspace_bytes(ctypes.byref(raw), ctypes.byref(out)) == -1
 
 
-@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(n_q_heads=18), dict(segment=5000)])
+@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(n_q_heads=18), dict(segment=(1 << 28) + 1)])
 def test_unsupported_shapes_say_so(bad):
     with pytest.raises(BuzzError) as e:
         workspace_bytes(cfg(**bad))
@@ -234,3 +234,31 @@ def test_decode_step_that_cannot_evict_fails_before_it_changes_anything():
             g.decode_step(None, None, None, None)
         assert e.value.code == -2
         assert g.lengths() == before
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_global_topk_sizes_match_oracle(seed):
+    """H2O-style baseline: after every eviction the cache holds sink + min(keep, middle) + window rows."""
+    from paper_2410_23079_amd import FLAG_GLOBAL_TOPK
+    r = np.random.default_rng(70 + seed)
+    k, w = int(r.integers(0, 5)), int(r.integers(0, 30))
+    B, T = int(r.integers(1, 40)), int(r.integers(1, 25))
+    N, steps = int(r.integers(0, 300)), 120
+    g = BuzzCache(cfg(sink=k, window=w, segment=7, keep=B, evict_every=T, old_stride=0, max_context=N + steps,
+                      flags=DRY | FLAG_GLOBAL_TOPK))
+    o = OracleCache(OracleConfig(1, 1, 1, 2, sink=k, window=w, segment=7, keep=B, evict_every=T, old_stride=0,
+                                 global_topk=True))
+    g.prefill(None, None, n_prompt=N)
+    o.prefill(np.zeros((1, 1, N, 2)), np.zeros((1, 1, N, 2)))
+    assert g.lengths() == o.lengths()
+    z = np.zeros((1, 1, 2))
+    for _ in range(steps):
+        g.decode_step(None, None, None, None)
+        o.decode_step(z, z, z)
+        assert g.lengths() == o.lengths()
+        assert g.lengths()[1] <= B and g.lengths()[0] <= k + B + w + T
+
+
+def test_segments_longer_than_a_wave_can_rank_are_accepted():
+    assert workspace_bytes(cfg(segment=5000, max_context=20000)) > 0
+    assert workspace_bytes(cfg(n_q_heads=2, segment=200000, keep=64, evict_every=200000, max_context=500000)) > 0

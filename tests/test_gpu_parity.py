@@ -189,8 +189,8 @@ def test_segment_longer_than_wave(keep):
     run(small(prompt=1500, decode_steps=10, sink=4, window=64, segment=200, keep=keep, evict_every=300, n_obs=16))
 
 
-def test_longest_supported_segment():
-    """segment = 4096 (the limit): two full segments and a ragged one at prefill, ties broken by index."""
+def test_longest_segment_one_wave_ranks():
+    """segment = 4096 (the most one wave ranks): two full segments and a ragged one at prefill, ties broken by index."""
     run(small(prompt=9000, decode_steps=6, sink=4, window=64, segment=4096, keep=9, evict_every=5000, n_obs=16))
 
 
@@ -233,6 +233,35 @@ def test_nan_and_infinite_scores_rank_as_stated(keep, old_stride):
                old_stride=old_stride, n_obs=12)
     st = run(wl, plant=plant_odd_scores)
     assert st["evictions"] == 3
+
+
+@pytest.mark.parametrize("segment,keep", [(5000, 7), (9000, 300)])
+def test_segments_longer_than_one_wave_can_rank(segment, keep):
+    """Segments beyond 4096 rows take the block-wide selection (radix select + prefix sum): two full segments and a
+    ragged one at prefill, ties everywhere (prompt scores of a short observation window are mostly equal)."""
+    run(small(prompt=2 * segment + 1500, decode_steps=4, sink=4, window=64, segment=segment, keep=keep,
+              evict_every=segment + 1000, n_obs=16))
+
+
+def test_long_segments_with_nan_and_infinite_scores():
+    st = run(small(prompt=11000, decode_steps=4, sink=4, window=64, segment=5000, keep=40, evict_every=6000, n_obs=12),
+             plant=plant_odd_scores)
+    assert st["evictions"] == 0                                  # everything happens in the prefill's selection
+
+
+@pytest.mark.parametrize("prompt,keep,G,dtype", [(700, 40, 1, "fp32"), (9000, 500, 1, "fp16"), (9000, 5000, 4, "bf16")])
+def test_global_topk_h2o_style(prompt, keep, G, dtype):
+    """Sec. 4.1's H2O baseline as a variant: the top `keep` accumulated scores among all rows between sink and
+    window survive every eviction (short middle: one wave ranks it; long middle: the block-wide selection)."""
+    wl = small(batch=1, n_kv_heads=2, n_q_heads=2 * G, head_dim=64, dtype=dtype, prompt=prompt, decode_steps=40,
+               sink=4, window=64, segment=16, keep=keep, evict_every=16, n_obs=24)
+    st = run(wl, global_topk=True)
+    assert st["evictions"] == 2
+
+
+def test_global_topk_with_odd_scores():
+    wl = small(prompt=600, decode_steps=40, sink=4, window=64, segment=16, keep=30, evict_every=16, n_obs=12)
+    run(wl, global_topk=True, plant=plant_odd_scores)
 
 
 def test_unbuffered_eviction_every_step():

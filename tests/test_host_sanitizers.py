@@ -49,6 +49,6 @@ def test_abi_host_code_under_sanitizers(tmp_path):
         from paper_2410_23079_amd.build import build
         build()
     exe = str(tmp_path / "sanitize_abi")
-    subprocess.run(["hipcc", "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-o", exe, drv_obj,
-                    api_obj, *others], check=True, capture_output=True)
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined",
+                    "-o", exe, drv_obj, api_obj, *others], check=True, capture_output=True)
     assert "sanitize_abi ok" in run_clean(exe)

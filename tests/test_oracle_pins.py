@@ -614,3 +614,56 @@ def test_prefill_trigger_boundary_literals(total):
         o.decode_step(z, z, z)
         sizes.append(o.lengths())
     assert sizes[6] == (12, 0, 7) and sizes[7] == (7, 2, 0) and sizes[8] == (8, 2, 1)
+
+
+# ---------------------------------------------------------------- H2O-style baseline (Sec. 4.1): global top-k by accumulated score
+@pytest.mark.parametrize("seed", range(8))
+def test_global_topk_matches_a_library_sort(seed):
+    """One segment over everything between sink and window: the survivors are the first `keep` entries of a
+    stable library sort by descending score (numpy.lexsort: ties keep index order), whatever was old or new."""
+    r = rng(600 + seed)
+    k, w, B, T, D = int(r.integers(0, 4)), int(r.integers(0, 7)), int(r.integers(1, 12)), int(r.integers(1, 9)), 2
+    N = int(r.integers(k + w + T, 90))
+    K = np.zeros((1, 1, N, D)); K[0, 0, :, 0] = np.arange(N)
+    score = r.integers(0, 6, size=N).astype(np.float64)
+    o = OracleCache(OracleConfig(1, 1, 1, D, sink=k, window=w, segment=3, keep=B, evict_every=T, old_stride=0,
+                                 auto_evict=False, global_topk=True))
+    o.prefill(K, -K, init_score=score[None, None])
+    pos = list(range(N))
+    if N - k - w >= T:
+        mid = np.arange(k, N - w)
+        order = np.lexsort((mid, -score[mid]))               # primary key: score descending; secondary: index
+        pos = list(range(k)) + sorted(mid[order[:B]].tolist()) + list(range(N - w, N))
+    assert list(o.export()[3][0, 0]) == pos
+    tok = N
+    for rnd in range(3):                                     # a few rounds: old survivors compete again with new rows
+        for _ in range(T):
+            row = np.zeros((1, 1, D)); row[0, 0, 0] = tok
+            o.decode_step(np.zeros((1, 1, D)), row, -row)
+            pos.append(tok); tok += 1
+        A = r.integers(0, 6, size=len(pos)).astype(np.float64)
+        o.set_scores(A[None, None])
+        o.evict()
+        n = len(pos)
+        mid = np.arange(k, n - w)
+        order = np.lexsort((mid, -A[mid]))
+        keep_idx = sorted(mid[order[:B]].tolist())
+        kept_scores, dropped = A[keep_idx], np.delete(A[mid], [i - k for i in keep_idx])
+        assert dropped.size == 0 or kept_scores.min() >= dropped.max()      # greedy: nothing evicted outranks a survivor
+        pos = [pos[j] for j in list(range(k)) + keep_idx + list(range(n - w, n))]
+        assert list(o.export()[3][0, 0]) == pos
+        assert o.lengths() == (len(pos), min(B, n - k - w), 0)
+
+
+def test_global_topk_literal_and_contrast_with_segments():
+    """Scores 0 1 2 ... 19 between a sink of 1 and a window of 2 (23 tokens): the H2O-style top 4 are the last four
+    middle tokens (17..20), where segments of 5 with one survivor each keep one token per hive (5, 10, 15, 20)."""
+    N, k, w = 23, 1, 2
+    z = np.zeros((1, 1, N, 1))
+    score = np.zeros((1, 1, N)); score[0, 0, 1:21] = np.arange(20)
+    h2o = OracleCache(OracleConfig(1, 1, 1, 1, sink=k, window=w, segment=5, keep=4, evict_every=1, global_topk=True))
+    h2o.prefill(z, z, init_score=score)
+    assert list(h2o.export()[3][0, 0]) == [0, 17, 18, 19, 20, 21, 22]
+    buzz = OracleCache(OracleConfig(1, 1, 1, 1, sink=k, window=w, segment=5, keep=1, evict_every=1, old_stride=1))
+    buzz.prefill(z, z, init_score=score)
+    assert list(buzz.export()[3][0, 0]) == [0, 5, 10, 15, 20, 21, 22]
