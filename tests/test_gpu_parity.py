@@ -352,80 +352,77 @@ def test_interval_sampling_of_new_tokens():
     run(small(prompt=300, decode_steps=48, keep=2), interval_new=True)
 
 
-def test_objective_on_clustered_keys():
-    """The same objective on config 5's recipe (keys and queries around 50 topic means per head), scaled down.
-    Heavy hitters are query-dependent there, so only the weakest claim is asserted: keeping segment winners
-    beats keeping nothing but sink and window."""
+def objective_table(wl, tag):
+    """Mean |O^ - O| / |O| over the decode steps (the eviction objective of Sec. 3.1, O = full attention written
+    out with torch in float64) for BUZZ, the two ablations of Sec. 4.3 and the baselines of Sec. 4.1 as variants of
+    this library: H2O-style (global top-k of accumulated scores) and sink + window, the last two also with the
+    budget BUZZ ends up with (H2O-style: keep = BUZZ's final survivor count; sink + window: the window widened by
+    it).  Returns {variant: (deviation, retained rows at the end)}."""
     import math
-    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_INTERVAL_NEW, BuzzCache
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_GLOBAL_TOPK, FLAG_INTERVAL_NEW, BuzzCache
     ls = lockstep()
-    wl = small("long131k", batch=1, n_kv_heads=4, n_q_heads=4, head_dim=128, dtype="bf16", prompt=4096, decode_steps=64,
-               sink=4, window=256, segment=32, keep=4, evict_every=32, n_obs=256)
     p, d = prompt_inputs(wl, device="cuda"), decode_inputs(wl, device="cuda")
-    Kall = torch.cat([p["K"], d["k"].permute(1, 2, 0, 3)], dim=2).double()
-    Vall = torch.cat([p["V"], d["v"].permute(1, 2, 0, 3)], dim=2).double()
-
-    def deviation(flags=0, **over):
-        c = BuzzCache(ls.buzz_config(wl, flags=FLAG_AUTO_EVICT | flags, **over))
-        c.prefill(p["K"], p["V"], q_obs=p["q_obs"])
-        out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device="cuda")
-        dev = 0.0
-        for t in range(wl.decode_steps):
-            c.decode_step(d["q"][t], d["k"][t], d["v"][t], out)
-            n = wl.prompt + t + 1
-            lg = torch.einsum("bhd,bhnd->bhn", d["q"][t].double(), Kall[:, :, :n]) / math.sqrt(wl.head_dim)
-            full = torch.einsum("bhn,bhnd->bhd", torch.softmax(lg, dim=-1), Vall[:, :, :n])
-            dev += float(((out.double() - full).norm(dim=-1) / full.norm(dim=-1)).mean())
-        c.close()
-        return dev / wl.decode_steps
-
-    buzz, no_max, window_only = deviation(), deviation(FLAG_INTERVAL_NEW), deviation(keep=0)
-    print(f"[objective, clustered] mean |O^ - O| / |O|: BUZZ {buzz:.4f}  no local max {no_max:.4f}  "
-          f"sink+window {window_only:.4f}", flush=True)
-    assert buzz < window_only
-
-
-def test_local_max_beats_the_ablations_on_the_papers_objective():
-    """Sec. 3.1 states the goal as keeping the evicted cache's attention output close to the full one.
-    On synthetic keys with planted heavy hitters, at one cache budget, BUZZ's output must be closer to full
-    attention than the no-local-max ablation and than sink + window alone (Sec. 4.3 reports the same
-    ordering in ROUGE, which needs the trained model and is not reproduced here)."""
-    import math
-    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_INTERVAL_NEW, BuzzCache
-    ls = lockstep()
-    wl = small(batch=2, n_kv_heads=4, n_q_heads=4, head_dim=64, dtype="fp32", prompt=2048, decode_steps=128,
-               sink=4, window=128, segment=16, keep=1, evict_every=16, n_obs=256, planted_frac=0.04)
-    p, d = prompt_inputs(wl, device="cuda"), decode_inputs(wl, device="cuda")
-    steps, N = wl.decode_steps, wl.prompt
-    Kall = torch.cat([p["K"], d["k"].permute(1, 2, 0, 3)], dim=2).double()      # [B,H,N+steps,D]
-    Vall = torch.cat([p["V"], d["v"].permute(1, 2, 0, 3)], dim=2).double()
+    steps, N, G = wl.decode_steps, wl.prompt, wl.group
+    Kall = torch.cat([p["K"], d["k"].permute(1, 2, 0, 3)], dim=2).double().repeat_interleave(G, dim=1)   # [B,Hq,N+steps,D]
+    Vall = torch.cat([p["V"], d["v"].permute(1, 2, 0, 3)], dim=2).double().repeat_interleave(G, dim=1)
     full = []
-    for t in range(steps):                                                     # full attention, written out
+    for t in range(steps):
         n = N + t + 1
         lg = torch.einsum("bhd,bhnd->bhn", d["q"][t].double(), Kall[:, :, :n]) / math.sqrt(wl.head_dim)
         full.append(torch.einsum("bhn,bhnd->bhd", torch.softmax(lg, dim=-1), Vall[:, :, :n]))
-    full = torch.stack(full)
 
     def deviation(flags=0, **over):
-        c = BuzzCache(ls.buzz_config(wl, flags=FLAG_AUTO_EVICT | flags, **over))
+        cfg = ls.buzz_config(wl, flags=FLAG_AUTO_EVICT | flags, **over)
+        c = BuzzCache(cfg)
         c.prefill(p["K"], p["V"], q_obs=p["q_obs"])
         out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device="cuda")
         dev = 0.0
         for t in range(steps):
             c.decode_step(d["q"][t], d["k"][t], d["v"][t], out)
             dev += float(((out.double() - full[t]).norm(dim=-1) / full[t].norm(dim=-1)).mean())
-        size = c.lengths()[0]
+        rows = c.lengths()[0]
         c.close()
-        return dev / steps, size
+        return dev / steps, rows
 
-    buzz, n_buzz = deviation()
-    no_max, n_no_max = deviation(FLAG_INTERVAL_NEW)
-    window_only, n_window = deviation(keep=0)
-    swapped, n_swapped = deviation(segment=(wl.segment + 1) // 2, old_stride=wl.segment)   # Sec. 4.3, first ablation
-    print(f"[objective] mean |O^ - O| / |O|: BUZZ {buzz:.4f} ({n_buzz} rows)  no local max {no_max:.4f} ({n_no_max})  "
-          f"sink+window {window_only:.4f} ({n_window})  swapped strides {swapped:.4f} ({n_swapped})", flush=True)
-    assert n_buzz == n_no_max
-    assert buzz < no_max < window_only
+    res = {"BUZZ": deviation()}
+    budget = res["BUZZ"][1] - wl.sink - wl.window             # survivors (and buffered rows) BUZZ ends with
+    res["no local max"] = deviation(FLAG_INTERVAL_NEW)
+    res["swapped strides"] = deviation(segment=(wl.segment + 1) // 2, old_stride=wl.segment)
+    res["H2O-style, same budget"] = deviation(FLAG_GLOBAL_TOPK, keep=budget)
+    res["sink + window, same budget"] = deviation(keep=0, window=wl.window + budget)
+    res["sink + window"] = deviation(keep=0)
+    print(f"[objective, {tag}] mean |O^ - O| / |O| (retained rows): "
+          + "; ".join(f"{k} {v[0]:.4f} ({v[1]})" for k, v in res.items()), flush=True)
+    return res
+
+
+def test_objective_on_clustered_keys():
+    """The objective on config 5's recipe (keys and queries around 50 topic means per head), scaled down.  Heavy
+    hitters are query-dependent there, so only the weakest claims are asserted: segment winners beat keeping
+    nothing but sink and window, at the small budget and at BUZZ's own."""
+    wl = small("long131k", batch=1, n_kv_heads=4, n_q_heads=4, head_dim=128, dtype="bf16", prompt=4096, decode_steps=64,
+               sink=4, window=256, segment=32, keep=4, evict_every=32, n_obs=256)
+    res = objective_table(wl, "clustered keys")
+    assert res["BUZZ"][0] < res["sink + window"][0]
+    assert res["BUZZ"][1] == res["no local max"][1]
+    assert abs(res["H2O-style, same budget"][1] - res["BUZZ"][1]) <= wl.evict_every
+    assert abs(res["sink + window, same budget"][1] - res["BUZZ"][1]) <= wl.evict_every
+
+
+def test_local_max_beats_the_ablations_on_the_papers_objective():
+    """Sec. 3.1 states the goal as keeping the evicted cache's attention output close to the full one.
+    On synthetic keys with planted heavy hitters, at one cache budget, BUZZ's output must be closer to full
+    attention than the no-local-max ablation and than sink + window (Sec. 4.3 reports the same ordering in ROUGE,
+    which needs the trained model and is not reproduced here).  The H2O-style baseline is reported at the same
+    budget; no order between it and BUZZ is asserted (planted keys are heavy for every query, which is the case
+    greedy global selection is made for; the paper's case against it rests on the structure of natural text)."""
+    wl = small(batch=2, n_kv_heads=4, n_q_heads=4, head_dim=64, dtype="fp32", prompt=2048, decode_steps=128,
+               sink=4, window=128, segment=16, keep=1, evict_every=16, n_obs=256, planted_frac=0.04)
+    res = objective_table(wl, "planted heavy keys")
+    assert res["BUZZ"][1] == res["no local max"][1]
+    assert res["BUZZ"][0] < res["no local max"][0] < res["sink + window"][0]
+    assert res["BUZZ"][0] < res["sink + window, same budget"][0]
+    assert abs(res["H2O-style, same budget"][1] - res["BUZZ"][1]) <= wl.evict_every
 
 
 @pytest.mark.parametrize("name,kw", [("tiny", {}), ("llama7b_layer", dict(batch=1, n_kv_heads=4, n_q_heads=4, decode_steps=256))])
