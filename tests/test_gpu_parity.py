@@ -162,6 +162,36 @@ def test_prefill_scores_when_logits_jump(G):
     print(f"[parity]   jumping logits G{G}: prefill-score {st['prefill_score']:.2e} out {st['out']:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configurations(seed):
+    """Seeded random shapes, cache parameters and variants through the whole lock-step protocol."""
+    r = np.random.default_rng(9000 + seed)
+    dtype = ["fp32", "fp16", "bf16"][seed % 3]
+    D = int(r.choice([64, 128, 256]))
+    G = int(r.choice([1, 1, 2, 3, 4, 8]))
+    Hkv = int(r.choice([1, 2, 3, 8]))
+    B = int(r.choice([1, 2]))
+    k, w = int(r.integers(0, 6)), int(r.integers(0, 200))
+    s = int(r.integers(1, 40))
+    c = int(r.integers(0, 5))
+    T = int(r.integers(1, 40))
+    old_stride = int(r.choice([1, 1, 0, 2, 3]))
+    N = int(r.integers(0, 1500))
+    steps = int(r.integers(T + 1, 3 * T + 30))
+    variant = seed % 4
+    kw = {}
+    if variant == 1:
+        kw["log_n"] = True
+    elif variant == 2 and c > 0:
+        kw["global_topk"] = True
+        c = int(r.integers(1, 60))
+    elif variant == 3:
+        kw["interval_new"] = True
+    wl = small(batch=B, n_kv_heads=Hkv, n_q_heads=Hkv * G, head_dim=D, dtype=dtype, prompt=N, decode_steps=steps,
+               sink=k, window=w, segment=s, keep=c, evict_every=T, old_stride=old_stride, n_obs=min(N, int(r.integers(0, 40))))
+    run(wl, deterministic=bool(seed % 2), device_merge=bool((seed // 2) % 2), **kw)
+
+
 # ------------------------------------------------------------------ degenerate cases of the method
 def test_keep_zero_streaming():
     run(small(prompt=200, decode_steps=40, keep=0, n_obs=8))
