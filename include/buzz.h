@@ -20,6 +20,8 @@
  *     void*, NULL = the default stream) and returns without synchronising.
  *     All sizes (rows retained, survivors, offsets) are functions of the
  *     configuration and the call history alone, so the host never reads back.
+ *     One exception: the first buzz_prefill of a process on a GPU waits once
+ *     for a short probe launch on `hip_stream` (see buzz_prefill).
  *   - Returns BUZZ_OK (0) or a negative buzz_status.  Arguments are validated
  *     before anything is enqueued: a failed call leaves the cache unchanged.
  *   - A handle must not be used from two threads at once.
@@ -141,6 +143,13 @@ int buzz_cache_create(const buzz_config_t* cfg, void* dev_workspace, size_t byte
  * once (all of them count as "new", Alg. 1 with n_old = 0); with s^ > 1 and an
  * explicit capacity the survivors are interval-sampled again until they fit.
  * Resets the handle: may be called again to start a new sequence.
+ * The first call of a process on a GPU also runs a probe launch on `hip_stream`
+ * and waits for it (tens of microseconds, once): it records which die every
+ * block of a small grid ran on, which decides whether decode steps may merge
+ * the splits of a (batch, kv-head) pair through one die's L2 (see
+ * BUZZ_FLAG_DEVICE_MERGE).  The probe uses the library's static device scratch
+ * array, like buzz_decode_step_static: do not run it concurrently with such a
+ * call on another stream.
  * Errors: BUZZ_EINVAL, BUZZ_ECAPACITY (n_prompt > max_context, survivors do
  *         not fit), BUZZ_EHIP.
  */
