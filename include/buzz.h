@@ -231,6 +231,16 @@ int buzz_cache_export(buzz_cache_t* cache, void* k, void* v, float* score, int32
 int buzz_cache_set_splits(buzz_cache_t* cache, int32_t n_splits);
 
 /*
+ * Failure-handling aid.  The die-local merge (see BUZZ_FLAG_DEVICE_MERGE) checks in every decode step that
+ * each block runs on the die the placement probe recorded for its launch-order number mod 8 (`die_map`:
+ * 4 bits per number), and turns the attention output of a (batch, kv-head) pair whose blocks do not into NaN.
+ * This call replaces the record the check compares with for one cache, so that a test can make the check
+ * fail from the host (every kernel still runs to its end); a negative value restores the probe's record.
+ * No effect where the die-local merge is not used.  Errors: BUZZ_EINVAL.
+ */
+int buzz_cache_override_die_map(buzz_cache_t* cache, int64_t die_map);
+
+/*
  * Benchmark aid: per-kernel device time measured with HIP events recorded on
  * the stream each kernel is launched on.  buzz_cache_profile(cache, 1) clears
  * the counters and starts recording (every launch then carries a start and a

@@ -27,7 +27,8 @@ DTYPE_CODES = {"fp32": 0, "fp16": 1, "bf16": 2}
 
 EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step",
            "buzz_decode_step_static", "buzz_evict",
-           "buzz_cache_destroy", "buzz_cache_len", "buzz_cache_export", "buzz_cache_set_splits", "buzz_cache_profile",
+           "buzz_cache_destroy", "buzz_cache_len", "buzz_cache_export", "buzz_cache_set_splits",
+           "buzz_cache_override_die_map", "buzz_cache_profile",
            "buzz_cache_profile_read", "buzz_bench_copy", "buzz_suggest_threshold", "buzz_strerror"]
 
 
@@ -105,6 +106,7 @@ def load_library():
     lib.buzz_cache_len.argtypes = [P, ctypes.POINTER(I64), ctypes.POINTER(I64), ctypes.POINTER(I64)]
     lib.buzz_cache_export.argtypes = [P, P, P, P, P, P]
     lib.buzz_cache_set_splits.argtypes = [P, ctypes.c_int32]
+    lib.buzz_cache_override_die_map.argtypes = [P, I64]
     lib.buzz_cache_profile.argtypes = [P, ctypes.c_int]
     lib.buzz_cache_profile_read.argtypes = [P, ctypes.POINTER(_Profile)]
     lib.buzz_bench_copy.argtypes = [P, P, ctypes.c_size_t, P]
@@ -205,6 +207,9 @@ class BuzzCache:
 
     def set_splits(self, n_splits: int):
         _check(self._lib.buzz_cache_set_splits(self._h, n_splits), "buzz_cache_set_splits")
+
+    def override_die_map(self, die_map: int):
+        _check(self._lib.buzz_cache_override_die_map(self._h, die_map), "buzz_cache_override_die_map")
 
     def profile(self, enable: bool):
         _check(self._lib.buzz_cache_profile(self._h, int(enable)), "buzz_cache_profile")

@@ -417,7 +417,7 @@ __device__ inline void finish_split_scoped(const AttnArgs& a, const SplitCtx& x,
             // recorded which die served block numbers 0..7 (die_map, 4 bits each); a block that finds itself
             // elsewhere says so in the ticket's upper half, and the merging block sees every earlier arrival's.
             int add = 1;
-            if (LOCAL && (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u) != ((a.die_map >> (4 * x.home)) & 7u)) add += 0x10000;   // XCC_ID
+            if (LOCAL && (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u) != ((a.die_map >> (4 * x.home)) & 15u)) add += 0x10000;   // XCC_ID
             const int before = __hip_atomic_fetch_add(a.ticket + unit, add, __ATOMIC_RELAXED, merge_scope<LOCAL>());
             *sm_ticket = before + (add & 0x10000);
         }

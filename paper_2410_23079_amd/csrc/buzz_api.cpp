@@ -209,6 +209,7 @@ struct buzz_cache {
     bool ready;
     int64_t sink_filled, n_old, tail, head, tokens_seen;
     int32_t user_splits;
+    int64_t die_map_override;   // >= 0: use this instead of the placement probe's record (failure-handling tests)
     // the score update of the last decode step is applied lazily (by the next step or by a flush)
     bool pending;
     int last_buf;   // logit / stat buffer the last decode step wrote
@@ -481,6 +482,7 @@ int buzz_cache_create(const buzz_config_t* cfg, void* dev_workspace, size_t byte
     c->ready = false;
     c->sink_filled = c->n_old = c->tail = c->head = c->tokens_seen = 0;
     c->user_splits = 0;
+    c->die_map_override = -1;
     c->pending = false;
     c->last_buf = 0;
     c->prof = false;
@@ -513,6 +515,13 @@ int buzz_cache_set_splits(buzz_cache_t* c, int32_t n_splits)
 {
     if (!alive(c) || n_splits < 0 || n_splits > c->L.s_cap) return BUZZ_EINVAL;
     c->user_splits = n_splits;
+    return BUZZ_OK;
+}
+
+int buzz_cache_override_die_map(buzz_cache_t* c, int64_t die_map)
+{
+    if (!alive(c) || die_map > 0xffffffffll) return BUZZ_EINVAL;
+    c->die_map_override = die_map < 0 ? -1 : die_map;
     return BUZZ_OK;
 }
 
@@ -725,6 +734,7 @@ int decode_step_impl(buzz_cache_t* c, const void* q, const void* k_new, const vo
         // the 8 dies
         a.xcd_local = (a.n_splits > 1 && L.units % 8 == 0 && !(cfg.flags & BUZZ_FLAG_DEVICE_MERGE) &&
                        die_local_ok(&a.die_map)) ? 1 : 0;
+        if (a.xcd_local && c->die_map_override >= 0) a.die_map = (uint32_t)c->die_map_override;
         if (hipError_t e = launch_attn_split(cfg.kv_dtype, cfg.head_dim, L.G, a, L.units, st,
                                              static_scratch ? Timing{} : prof_pair(c, 0)))
             return hip_rc(e);

@@ -118,6 +118,33 @@ def test_split_merge_through_one_die_or_device_memory(G, dtype, heads, device_me
     run(wl, device_merge=device_merge, deterministic=False)
 
 
+def test_die_local_merge_refuses_blocks_on_an_unexpected_die():
+    """The guard of the die-local merge, forced from the host: with a wrong record of which die serves which
+    launch-order number every block reports a mismatch and the outputs of the step are NaN, not numbers; the
+    kernels run to their end, and with the probe's record restored the cache goes on as if nothing had happened
+    (the stored rows and scores never depended on the merge)."""
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_DETERMINISTIC, BuzzCache
+    ls = lockstep()
+    wl = small(batch=1, n_kv_heads=8, n_q_heads=32, head_dim=128, dtype="bf16", prompt=2600, decode_steps=12,
+               sink=4, window=1100, segment=16, keep=3, evict_every=16, n_obs=24)
+    p, d = prompt_inputs(wl, device="cuda"), decode_inputs(wl, device="cuda")
+    a, b = (BuzzCache(ls.buzz_config(wl, flags=FLAG_AUTO_EVICT | FLAG_DETERMINISTIC)) for _ in range(2))
+    for c in (a, b):
+        c.prefill(p["K"], p["V"], q_obs=p["q_obs"])
+    out_a, out_b = (torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device="cuda") for _ in range(2))
+    for t in range(wl.decode_steps):
+        wrong = t in (3, 4)
+        b.override_die_map(0x88888888 if wrong else -1)          # die 8 does not exist: no block can match
+        a.decode_step(d["q"][t], d["k"][t], d["v"][t], out_a)
+        b.decode_step(d["q"][t], d["k"][t], d["v"][t], out_b)
+        if wrong:
+            assert torch.isnan(out_b).all() and torch.isfinite(out_a).all()
+        else:
+            assert torch.equal(out_a, out_b)
+    for x, y in zip(a.export(), b.export()):
+        assert torch.equal(x, y)
+
+
 @pytest.mark.parametrize("deterministic", [True, False])
 @pytest.mark.parametrize("G,dtype", [(1, "bf16"), (4, "fp16"), (2, "fp32")])
 def test_more_units_than_compute_units(deterministic, G, dtype):
