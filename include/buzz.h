@@ -224,6 +224,19 @@ int buzz_cache_len(const buzz_cache_t* cache, int64_t* n, int64_t* n_old, int64_
 int buzz_cache_export(buzz_cache_t* cache, void* k, void* v, float* score, int32_t* pos, void* hip_stream);
 
 /*
+ * The inverse of buzz_cache_export (checkpoint / resume): load `n` retained rows per (batch, kv-head), given in
+ * cache order [sink | old | new | window] with the layouts buzz_cache_export writes, of which `n_old` are old
+ * rows, into a cache of the same configuration; `tokens_seen` = prompt + decoded tokens so far (it numbers the
+ * next token and feeds the log-n scale).  Replaces whatever the handle held, like buzz_prefill; decode steps
+ * continue from there exactly as they would have on the exporting cache (same rows, scores, sizes; sums may
+ * differ in the last bits because the rows sit at other places of the ring).
+ * Errors: BUZZ_EINVAL (null pointers, n_old > n, tokens_seen < n, old rows without a full sink),
+ *         BUZZ_ECAPACITY (more old rows, buffered rows or tokens than the cache was sized for), BUZZ_EHIP.
+ */
+int buzz_cache_import(buzz_cache_t* cache, const void* k, const void* v, const float* score, const int32_t* pos,
+                      int64_t n, int64_t n_old, int64_t tokens_seen, void* hip_stream);
+
+/*
  * Tuning knob: number of key-range splits per (batch, kv-head) used by the
  * split softmax of the decode kernel; 0 restores the automatic choice.
  * Errors: BUZZ_EINVAL (negative, or above what the workspace was sized for).

@@ -27,7 +27,7 @@ DTYPE_CODES = {"fp32": 0, "fp16": 1, "bf16": 2}
 
 EXPORTS = ["buzz_workspace_bytes", "buzz_cache_create", "buzz_prefill", "buzz_decode_step",
            "buzz_decode_step_static", "buzz_evict",
-           "buzz_cache_destroy", "buzz_cache_len", "buzz_cache_export", "buzz_cache_set_splits",
+           "buzz_cache_destroy", "buzz_cache_len", "buzz_cache_export", "buzz_cache_import", "buzz_cache_set_splits",
            "buzz_cache_override_die_map", "buzz_cache_profile",
            "buzz_cache_profile_read", "buzz_bench_copy", "buzz_suggest_threshold", "buzz_strerror"]
 
@@ -105,6 +105,7 @@ def load_library():
     lib.buzz_cache_destroy.argtypes = [P]
     lib.buzz_cache_len.argtypes = [P, ctypes.POINTER(I64), ctypes.POINTER(I64), ctypes.POINTER(I64)]
     lib.buzz_cache_export.argtypes = [P, P, P, P, P, P]
+    lib.buzz_cache_import.argtypes = [P, P, P, P, P, I64, I64, I64, P]
     lib.buzz_cache_set_splits.argtypes = [P, ctypes.c_int32]
     lib.buzz_cache_override_die_map.argtypes = [P, I64]
     lib.buzz_cache_profile.argtypes = [P, ctypes.c_int]
@@ -218,6 +219,12 @@ class BuzzCache:
         p = _Profile()
         _check(self._lib.buzz_cache_profile_read(self._h, ctypes.byref(p)), "buzz_cache_profile_read")
         return {k: getattr(p, k) for k, _ in _Profile._fields_}
+
+    def import_rows(self, k, v, score, pos, n_old: int, tokens_seen: int, stream=None, n=None):
+        """Load retained rows (as ``export`` returns them) into this cache; ``n`` only for dry-run caches."""
+        n = k.shape[2] if n is None else n
+        _check(self._lib.buzz_cache_import(self._h, _ptr(k), _ptr(v), _ptr(score), _ptr(pos), n, n_old, tokens_seen,
+                                           self._stream(stream)), "buzz_cache_import")
 
     def export(self, stream=None):
         """Retained rows in cache order: (K, V, score, pos) as new GPU tensors."""

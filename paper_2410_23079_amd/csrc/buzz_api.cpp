@@ -787,6 +787,46 @@ int buzz_cache_export(buzz_cache_t* c, void* k, void* v, float* score, int32_t* 
     return hip_rc(launch_gather_rows(g, c->L.units, (hipStream_t)hip_stream));
 }
 
+int buzz_cache_import(buzz_cache_t* c, const void* k, const void* v, const float* score, const int32_t* pos,
+                      int64_t n, int64_t n_old, int64_t tokens_seen, void* hip_stream)
+{
+    if (!alive(c) || n < 0 || n_old < 0 || n_old > n || tokens_seen < n) return BUZZ_EINVAL;
+    if (!c->dry && n > 0 && (!k || !v || !score || !pos)) return BUZZ_EINVAL;
+    const buzz_config_t& cfg = c->cfg;
+    const Layout& L = c->L;
+    if (tokens_seen > cfg.max_context || n_old > L.old_cap) return BUZZ_ECAPACITY;
+    // Alg. 1 fills the sink first, and old rows only exist once the sink is full
+    const int64_t sink_rows = n - n_old < cfg.sink ? n - n_old : cfg.sink;
+    if (n_old > 0 && sink_rows < cfg.sink) return BUZZ_EINVAL;
+    const int64_t tail_rows = n - sink_rows - n_old;
+    if (tail_rows > L.ring_cap) return BUZZ_ECAPACITY;
+    if (!c->dry) {
+        hipStream_t st = (hipStream_t)hip_stream;
+        if (int rc = probe_die_placement(st)) return rc;
+        if (hipError_t e = launch_fill_f32(c->at<float>(L.ticket), nullptr, L.units, st)) return hip_rc(e);
+        GatherArgs g{};
+        g.srcK = k; g.srcV = v; g.srcScore = score; g.srcPos = pos;
+        g.src_unit_rows = n; g.src_step = 1; g.sel_step = 1;
+        g.dstK = c->at<char>(L.K); g.dstV = c->at<char>(L.V);
+        g.dstScore = c->at<float>(L.score); g.dstPos = c->at<int32_t>(L.pos);
+        g.dst_unit_rows = L.cap; g.row_bytes = L.row_bytes;
+        GatherArgs front = g;                                  // sink and old rows: the linear region
+        front.src_start = 0; front.dst_start = 0; front.n_rows = (int32_t)(sink_rows + n_old);
+        if (hipError_t e = launch_gather_rows(front, L.units, st)) return hip_rc(e);
+        GatherArgs ring = g;                                   // buffered new rows and the window: the ring, from its base
+        ring.src_start = (int32_t)(sink_rows + n_old); ring.dst_start = L.ring_base; ring.n_rows = (int32_t)tail_rows;
+        if (hipError_t e = launch_gather_rows(ring, L.units, st)) return hip_rc(e);
+    }
+    c->pending = false;
+    c->sink_filled = sink_rows;
+    c->n_old = n_old;
+    c->tail = tail_rows;
+    c->head = 0;
+    c->tokens_seen = tokens_seen;
+    c->ready = true;
+    return BUZZ_OK;
+}
+
 int buzz_cache_profile(buzz_cache_t* c, int enable)
 {
     if (!alive(c)) return BUZZ_EINVAL;

@@ -262,3 +262,26 @@ def test_global_topk_sizes_match_oracle(seed):
 def test_segments_longer_than_a_wave_can_rank_are_accepted():
     assert workspace_bytes(cfg(segment=5000, max_context=20000)) > 0
     assert workspace_bytes(cfg(n_q_heads=2, segment=200000, keep=64, evict_every=200000, max_context=500000)) > 0
+
+
+def test_import_restores_the_bookkeeping():
+    """Checkpoint / resume: a cache loaded with another cache's sizes continues with the same sizes (Alg. 1)."""
+    a = BuzzCache(cfg(max_context=3000))
+    a.prefill(None, None, n_prompt=700)
+    for _ in range(45):
+        a.decode_step(None, None, None, None)
+    n, n_old, new = a.lengths()
+    b = BuzzCache(cfg(max_context=3000))
+    b.import_rows(None, None, None, None, n_old=n_old, tokens_seen=745, n=n)
+    assert b.lengths() == a.lengths()
+    for _ in range(200):
+        a.decode_step(None, None, None, None)
+        b.decode_step(None, None, None, None)
+        assert a.lengths() == b.lengths()
+    lib = load_library()
+    h = b._h
+    assert lib.buzz_cache_import(h, None, None, None, None, 10, 11, 20, None) == -1      # n_old > n
+    assert lib.buzz_cache_import(h, None, None, None, None, 10, 0, 5, None) == -1        # fewer tokens seen than rows
+    assert lib.buzz_cache_import(h, None, None, None, None, 6, 3, 6, None) == -1         # old rows without a full sink
+    assert lib.buzz_cache_import(h, None, None, None, None, 10, 0, 5000, None) == -2     # beyond max_context
+    assert lib.buzz_cache_import(h, None, None, None, None, 2500, 0, 2500, None) == -2   # more buffered rows than the ring holds

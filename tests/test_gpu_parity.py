@@ -118,6 +118,39 @@ def test_split_merge_through_one_die_or_device_memory(G, dtype, heads, device_me
     run(wl, device_merge=device_merge, deterministic=False)
 
 
+@pytest.mark.parametrize("G,dtype,old_stride", [(1, "fp32", 1), (4, "bf16", 1), (1, "fp16", 0)])
+def test_export_then_import_resumes_the_cache(G, dtype, old_stride):
+    """Checkpoint / resume: rows exported from a running cache and imported into a fresh one give the same
+    attention outputs (same rows, other places in the ring: sums within rounding), the same evictions and the
+    same final rows."""
+    from paper_2410_23079_amd import FLAG_AUTO_EVICT, FLAG_DETERMINISTIC, BuzzCache
+    ls = lockstep()
+    wl = small(batch=2, n_kv_heads=2, n_q_heads=2 * G, head_dim=128, dtype=dtype, prompt=900, decode_steps=90,
+               sink=4, window=100, segment=16, keep=2, evict_every=16, old_stride=old_stride, n_obs=24)
+    p, d = prompt_inputs(wl, device="cuda"), decode_inputs(wl, device="cuda")
+    a, b = (BuzzCache(ls.buzz_config(wl, flags=FLAG_AUTO_EVICT | FLAG_DETERMINISTIC)) for _ in range(2))
+    a.prefill(p["K"], p["V"], q_obs=p["q_obs"])
+    out_a, out_b = (torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device="cuda") for _ in range(2))
+    first = 37                                                  # mid-cycle: buffered rows, ring head moved twice
+    for t in range(first):
+        a.decode_step(d["q"][t], d["k"][t], d["v"][t], out_a)
+    K, V, S, P = a.export()
+    n, n_old, _ = a.lengths()
+    b.import_rows(K, V, S, P, n_old=n_old, tokens_seen=wl.prompt + first)
+    assert a.lengths() == b.lengths()
+    for t in range(first, wl.decode_steps):
+        a.decode_step(d["q"][t], d["k"][t], d["v"][t], out_a)
+        b.decode_step(d["q"][t], d["k"][t], d["v"][t], out_b)
+        e = ls.rel_err(out_b.double().cpu().numpy(), out_a.double().cpu().numpy())
+        assert e <= ls.REPRO_TOL, f"step {t}: resumed cache differs by {e}"
+        assert a.lengths() == b.lengths()
+    for i, (x, y) in enumerate(zip(a.export(), b.export())):
+        if i == 2:
+            assert torch.allclose(x, y, rtol=ls.REPRO_TOL, atol=ls.REPRO_TOL)
+        else:
+            assert torch.equal(x, y)
+
+
 def test_die_local_merge_refuses_blocks_on_an_unexpected_die():
     """The guard of the die-local merge, forced from the host: with a wrong record of which die serves which
     launch-order number every block reports a mismatch and the outputs of the step are NaN, not numbers; the
