@@ -34,8 +34,9 @@ def _oracle(wl, p):
     return o
 
 
-BIG = dict(batch=1, n_kv_heads=4, n_q_heads=16, head_dim=128, dtype="bf16", prompt=6000, decode_steps=40,
-           sink=4, window=2000, segment=16, keep=2, evict_every=16, n_obs=32)      # ~20 splits per unit, matrix cores
+BIG = dict(batch=1, n_kv_heads=8, n_q_heads=32, head_dim=128, dtype="bf16", prompt=6000, decode_steps=40,
+           sink=4, window=2000, segment=16, keep=2, evict_every=16, n_obs=32)      # ~20 splits per unit, matrix cores,
+                                                                                   # a unit's blocks on one die
 SMALL = dict(batch=1, n_kv_heads=2, n_q_heads=2, head_dim=64, dtype="fp16", prompt=700, decode_steps=40,
              sink=2, window=300, segment=8, keep=1, evict_every=8, n_obs=8)        # 3 splits per unit, vector ALU
 
