@@ -68,15 +68,23 @@ def make_caches(wl, layers, max_context, splits, flags):
 
 
 def prefill_all(wl, caches, device):
+    """Prefill every layer's cache from its seeded prompt; returns the median time of one layer's buzz_prefill
+    (prompt scoring with the workload's n_obs, sampling, compaction; not part of the decode metric)."""
     import torch
     from workloads import prompt_inputs
+    times = []
     for layer, c in enumerate(caches):
         p = prompt_inputs(wl, layer=layer, device=device)
         n_obs = min(wl.n_obs, wl.prompt)
         q_obs = p["q_obs"][:, :, p["q_obs"].shape[2] - n_obs:, :].contiguous() if n_obs else None
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         c.prefill(p["K"], p["V"], q_obs=q_obs)
         torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
         del p
+    times.sort()
+    return times[len(times) // 2] * 1e3
 
 
 def step_views(dec):
@@ -140,7 +148,7 @@ def measure(wl, layers, steps, warmup, splits, streaming, device, profile, copy_
     out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device=device)
     flags = FLAG_AUTO_EVICT | (FLAG_STREAMING if streaming else 0) | (FLAG_DEVICE_MERGE if device_merge else 0)
     caches = make_caches(wl, layers, wl.prompt + budget, splits, flags)
-    prefill_all(wl, caches, device)
+    prefill_ms = prefill_all(wl, caches, device)
     if copy_mib:
         from paper_2410_23079_amd import bench_copy
         src = torch.full((copy_mib << 20,), 7, dtype=torch.uint8, device=device)
@@ -159,6 +167,7 @@ def measure(wl, layers, steps, warmup, splits, streaming, device, profile, copy_
     elapsed = time.perf_counter() - t0
     n_end = caches[0].lengths()[0]
     res = {"steps_per_s": steps / elapsed, "ms_per_step": elapsed / steps * 1e3, "rolled_steps": rolled,
+           "prefill_ms_per_layer": prefill_ms,
            "evictions_in_timed_steps": timed_evictions, "retained_rows_end": n_end}
 
     # second pass: the next K steps, aligned the same way, with HIP events around every kernel (on the launch stream)
@@ -318,6 +327,7 @@ def main():
             / (res["ms_per_step"] * 1e-3)
     extra["evictions_in_timed_steps"] = res["evictions_in_timed_steps"]
     extra["rolled_steps"] = res["rolled_steps"]
+    extra["prefill_ms_per_layer"] = res["prefill_ms_per_layer"]
     if args.prefill_obs:
         extra["prefill_scoring"] = prefill_scoring(wl, res["_caches"][0], min(args.prefill_obs, wl.prompt), device)
     n_end = res["retained_rows_end"]
