@@ -323,44 +323,47 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
         const int per_part = (n_chunks + a.key_splits - 1) / a.key_splits;
         const int c_begin = part * per_part, c_end = min(n_chunks, c_begin + per_part);   // this block's chunks
         // Lazy reference: a lane sums exp2(s * scale - ref) against a reference that only moves when it has
-        // to.  A 16 x 16 tile whose sum (for any of its queries) exceeds kRefSlack is redone the classic way:
-        // the reference rises to the running maximum and the sum so far is rescaled.  Elsewhere a tile costs
-        // one fma, one exp2 and one add per element and none of the maximum bookkeeping.  The reference
-        // starts so low that the first tile with a visible key always takes the classic path.  m[] holds
-        // the reference in scaled (log2) units.
-        auto consume_as = [&](const u32x4 (&kf)[QP], int k0, auto masked_tag) {
+        // to.  A chunk costs one fma, one exp2 and one add per element, straight-line code per 16 x 64 tile
+        // (four independent chains of matrix instructions and the vector work on their results) with none
+        // of the maximum bookkeeping, and one test at its end: if a sum of the wave has grown past kRefSlack
+        // (or overflowed), the sums go back to their values before the chunk and the chunk is redone the
+        // classic way, tile by tile: the reference rises to the running maximum and the sum so far is
+        // rescaled.  The reference starts so low that the first chunk with a visible key always takes the
+        // classic path; after it the test fails only when a logit exceeds its lane's reference by about 30
+        // (log2 units).  m[] holds the reference in scaled (log2) units.
+        auto products = [&](const u32x4 (&kf)[QP], int ct) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int p = 0; p < QP; ++p) acc = mma16<DT>(kf[p], qf[ct][p], acc);
+            return acc;
+        };
+        // causal: key k0 + 4q + v against this lane's query.  An invisible key contributes 0 through a
+        // select, not through a product of -inf: the log-n scale of the first prompt query is 0.
+        auto tile_sum = [&](const f32x4& acc, int ct, int k0, auto masked_tag) {
             constexpr bool MASKED = decltype(masked_tag)::value;
+            float e[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                e[v] = __builtin_amdgcn_exp2f(fmaf(acc[v], scale[ct], -m[ct]));
+                if (MASKED && k0 + 4 * q + v > pos[ct]) e[v] = 0.f;
+            }
+            return (e[0] + e[1]) + (e[2] + e[3]);
+        };
+        auto add_tile = [&](const u32x4 (&kf)[QP], int k0, auto masked_tag) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) l[ct] += tile_sum(products(kf, ct), ct, k0, masked_tag);
+        };
+        auto add_tile_classic = [&](const u32x4 (&kf)[QP], int k0) {
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                const f32x4 acc = products(kf, ct);
+                float top = kRefStart;
 #pragma unroll
-                for (int p = 0; p < QP; ++p) acc = mma16<DT>(kf[p], qf[ct][p], acc);
-                // causal: key k0 + 4q + v against this lane's query.  An invisible key contributes 0 through a
-                // select, not through a product of -inf: the log-n scale of the first prompt query is 0.
-                bool vis[4];
-                float sum = 0.f;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    vis[v] = !MASKED || k0 + 4 * q + v <= pos[ct];
-                    const float e = __builtin_amdgcn_exp2f(fmaf(acc[v], scale[ct], -m[ct]));
-                    sum += vis[v] ? e : 0.f;
-                }
-                // wave-uniform and rare after the first tiles; !(<=) also catches a sum that overflowed
-                if (__builtin_amdgcn_ballot_w64(!(sum <= kRefSlack)) != 0) {
-                    float top = kRefStart;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) top = fmaxf(top, vis[v] ? acc[v] * scale[ct] : kRefStart);
-                    const float ref = fmaxf(m[ct], top);   // unchanged where the tile brought nothing larger
-                    l[ct] *= __builtin_amdgcn_exp2f(m[ct] - ref);   // exactly 1 where the reference stands still
-                    m[ct] = ref;
-                    sum = 0.f;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const float e = __builtin_amdgcn_exp2f(fmaf(acc[v], scale[ct], -ref));
-                        sum += vis[v] ? e : 0.f;
-                    }
-                }
-                l[ct] += sum;
+                for (int v = 0; v < 4; ++v) top = fmaxf(top, k0 + 4 * q + v <= pos[ct] ? acc[v] * scale[ct] : kRefStart);
+                // unchanged, and the factor exactly 1, where the tile brought nothing larger
+                l[ct] *= __builtin_amdgcn_exp2f(fminf(m[ct] - top, 0.f));
+                m[ct] = fmaxf(m[ct], top);
+                l[ct] += tile_sum(acc, ct, k0, std::true_type{});
             }
         };
         MC::request(staged, Kb, c_begin * CH, a.N - 1);
@@ -370,6 +373,9 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
             const bool more = c + 1 < c_end;
             if (more) MC::request(staged, Kb, (c + 1) * CH, a.N - 1);
             if (active) {
+                float l_in[CT];
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) l_in[ct] = l[ct];
                 // (head_dim <= 128) the operand of tile i + 1 leaves LDS while tile i is computed; reading
                 // past the wave's last tile stays inside the buffer and is never used
                 u32x4 kf[2][QP];
@@ -381,8 +387,23 @@ __global__ __launch_bounds__(256) void obs_mfma_kernel(const ObsArgs a)
                     if (!AHEAD && tile > 0) MC::fetch(kf[0], sm_rows[c & 1], tile, j, q);
                     if (k0 <= k_last) {
                         // wave-uniform: does a causal boundary or the end of the query list cross this tile?
-                        if (k0 + 15 > k_free || t_base + kMmaCols > t_end) consume_as(kf[AHEAD ? tile & 1 : 0], k0, std::true_type{});
-                        else consume_as(kf[AHEAD ? tile & 1 : 0], k0, std::false_type{});
+                        if (k0 + 15 > k_free || t_base + kMmaCols > t_end) add_tile(kf[AHEAD ? tile & 1 : 0], k0, std::true_type{});
+                        else add_tile(kf[AHEAD ? tile & 1 : 0], k0, std::false_type{});
+                    }
+                }
+                // the sums are nonnegative: their total passes the test only if each of them does; !(<=) also
+                // catches a sum that overflowed or is not a number
+                const float total = (l[0] + l[1]) + (l[2] + l[3]);
+                static_assert(CT == 4, "the test adds four sums");
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(total <= kRefSlack)) != 0, 0)) {
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) l[ct] = l_in[ct];
+#pragma unroll 1
+                    for (int tile = 0; tile < CH / 16; ++tile) {
+                        const int k0 = c * CH + 16 * tile;
+                        if (k0 > k_last) break;
+                        MC::fetch(kf[0], sm_rows[c & 1], tile, j, q);
+                        add_tile_classic(kf[0], k0);
                     }
                 }
             }
