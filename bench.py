@@ -348,7 +348,7 @@ def main():
     line = {
         "metric": "decode_steps_per_sec_incl_eviction", "value": res["steps_per_s"], "unit": "steps/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": f"{wl.dtype} storage, f32 accumulate", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "kv_dtype": wl.dtype, "data": "synthetic",
         "tokens_per_s": res["steps_per_s"] * wl.batch,
         "config": {"workload": wl.name, "layers": layers, "batch": wl.batch, "n_q_heads": wl.n_q_heads,
                    "n_kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "prompt": wl.prompt, "sink": wl.sink,
