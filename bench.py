@@ -311,16 +311,18 @@ def main():
     roofline = None
     extra = {}
     if not args.no_profile_pass:
-        traffic = None                                             # HBM bytes per launch from rocprofv3 --pmc runs
+        traffic = traffic_parts = None                             # HBM bytes per launch from rocprofv3 --pmc runs
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
         if os.path.exists(tpath):
             t = json.load(open(tpath)).get(wl.name)
             if t and layers == wl.layers and not args.splits:
-                traffic = {"fetch_bytes": t["fetch_bytes_per_launch"], "write_bytes": t["write_bytes_per_launch"],
-                           "source": t["source"]}
+                traffic = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
+                traffic_parts = {"fetch_bytes": t["fetch_bytes_per_launch"], "write_bytes": t["write_bytes_per_launch"],
+                                 "source": t["source"]}
         roofline = {"bound": "hbm", "kernel": res["kernel"], "achieved": res["achieved_gbs"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": res["frac"], "avg_launch_us": res["avg_launch_us"],
-                    "launches": res["launches"], "bytes_per_launch": res["bytes_per_launch"], "traffic": traffic}
+                    "launches": res["launches"], "bytes_per_launch": res["bytes_per_launch"], "traffic": traffic,
+                    "traffic_parts": traffic_parts}
         extra = {k: res[k] for k in ("evictions", "evict_avg_us", "evict_us_per_step", "evict_share_of_step",
                                      "launch_gap_us")}
         extra["step_bytes_over_peak_over_step_time"] = (res["bytes_per_launch"] * layers / HBM_PEAK_GBS / 1e9) \
