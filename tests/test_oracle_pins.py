@@ -76,9 +76,9 @@ def test_softmax_scale_argument_and_default():
 
 
 # ---------------------------------------------------------------- accumulated score = column sums of the causal matrix
-@pytest.mark.parametrize("G,n_obs", [(1, 20), (2, 7), (2, 0)])
-def test_prefill_and_decode_scores_are_causal_column_sums(G, n_obs):
-    B, Hkv, D, N, steps = 1, 2, 8, 20, 6
+@pytest.mark.parametrize("G,n_obs,B", [(1, 20, 1), (2, 7, 1), (2, 0, 1), (2, 9, 3)])
+def test_prefill_and_decode_scores_are_causal_column_sums(G, n_obs, B):
+    Hkv, D, N, steps = 2, 8, 20, 6
     Hq = Hkv * G
     x = make(B, Hq, Hkv, D, N, steps, 3)
     init = rng(4).random((B, Hkv, N))
@@ -92,12 +92,63 @@ def test_prefill_and_decode_scores_are_causal_column_sums(G, n_obs):
     qs = np.concatenate([x["q_obs"][:, :, N - n_obs:, :], np.moveaxis(x["q"], 0, 2)], axis=2)  # [B,Hq,n_obs+steps,D]
     qpos = np.concatenate([np.arange(N - n_obs, N), np.arange(N, N + steps)])
     expect = np.concatenate([init, np.zeros((B, Hkv, steps))], axis=2)
-    for h in range(Hq):
-        logits = torch.from_numpy(qs[0, h] @ Kall[0, h // G].T / math.sqrt(D))
-        mask = torch.from_numpy(np.arange(N + steps)[None, :] > qpos[:, None])
-        P = torch.softmax(logits.masked_fill(mask, -math.inf), dim=-1).numpy()
-        expect[0, h // G] += P.sum(axis=0)
+    for b in range(B):
+        for h in range(Hq):
+            logits = torch.from_numpy(qs[b, h] @ Kall[b, h // G].T / math.sqrt(D))
+            mask = torch.from_numpy(np.arange(N + steps)[None, :] > qpos[:, None])
+            P = torch.softmax(logits.masked_fill(mask, -math.inf), dim=-1).numpy()
+            expect[b, h // G] += P.sum(axis=0)
     np.testing.assert_allclose(A, expect, rtol=1e-11, atol=1e-13)
+
+
+def test_exported_rows_are_the_input_rows_at_the_exported_positions():
+    """Every (batch, kv-head) unit's exported K / V rows are the caller's rows at the exported token
+    positions (the cache stores keys and values as given, eq. 2), also after evictions."""
+    B, Hq, Hkv, D, N, steps = 2, 6, 3, 8, 70, 25
+    x = make(B, Hq, Hkv, D, N, steps, 91)
+    o = OracleCache(OracleConfig(B, Hq, Hkv, D, sink=3, window=7, segment=5, keep=2, evict_every=6, old_stride=2))
+    o.prefill(x["K"], x["V"], q_obs=x["q_obs"][:, :, -4:, :])
+    Kall = np.concatenate([x["K"], np.moveaxis(x["k"], 0, 2)], axis=2)
+    Vall = np.concatenate([x["V"], np.moveaxis(x["v"], 0, 2)], axis=2)
+    for t in range(steps):
+        o.decode_step(x["q"][t], x["k"][t], x["v"][t])
+        K, V, _, pos = o.export()
+        for b in range(B):
+            for h in range(Hkv):
+                assert (K[b, h] == Kall[b, h][pos[b, h]]).all() and (V[b, h] == Vall[b, h][pos[b, h]]).all()
+
+
+def test_set_scores_reaches_every_unit():
+    """Scores written with set_scores come back from export unit by unit, and the next eviction ranks by them."""
+    B, Hq, Hkv, D, N = 2, 2, 2, 4, 30
+    x = make(B, Hq, Hkv, D, N, 1, 92)
+    o = OracleCache(OracleConfig(B, Hq, Hkv, D, sink=2, window=4, segment=6, keep=1, evict_every=1000, old_stride=1,
+                                 auto_evict=False))
+    o.prefill(x["K"], x["V"])
+    n = o.lengths()[0]
+    A = rng(93).random((B, Hkv, n))
+    o.set_scores(A)
+    assert (o.export()[2] == A).all()
+    o.evict()
+    pos = o.export()[3]
+    for b in range(B):
+        for h in range(Hkv):
+            want = [2 + i + int(np.argmax(A[b, h, 2 + i:min(2 + i + 6, n - 4)])) for i in range(0, n - 6, 6)]
+            assert list(pos[b, h, 2:-4]) == want
+
+
+def test_softmax_is_taken_relative_to_the_largest_logit():
+    """Logits far outside exp's range still give the library's probabilities (eq. 3 evaluated stably)."""
+    B, Hq, Hkv, D = 1, 1, 1, 2
+    K = np.array([[[[0.0, 0.0], [400.0, 0.0], [401.0, 0.0]]]])
+    V = np.array([[[[1.0, 0.0], [0.0, 1.0], [0.0, 3.0]]]])
+    o = OracleCache(OracleConfig(B, Hq, Hkv, D, sink=1, window=100, segment=4, softmax_scale=1.0))
+    o.prefill(K, V)
+    q = np.array([[[2.0, 0.0]]]); k = np.array([[[-400.0, 0.0]]]); v = np.array([[[5.0, 5.0]]])
+    out = o.decode_step(q, k, v)
+    p = torch.softmax(torch.tensor([0.0, 800.0, 802.0, -800.0], dtype=torch.float64), 0).numpy()
+    np.testing.assert_allclose(out[0, 0], p @ np.array([[1.0, 0.0], [0.0, 1.0], [0.0, 3.0], [5.0, 5.0]]), rtol=1e-13)
+    np.testing.assert_allclose(o.export()[2][0, 0], p, rtol=1e-13, atol=0)
 
 
 # ---------------------------------------------------------------- P8: probability mass
