@@ -24,6 +24,10 @@
  *     for a short probe launch on `hip_stream` (see buzz_prefill).
  *   - Returns BUZZ_OK (0) or a negative buzz_status.  Arguments are validated
  *     before anything is enqueued: a failed call leaves the cache unchanged.
+ *     Every call also checks, before it enqueues anything, that the rows it is
+ *     about to touch lie inside the regions of the workspace layout, and
+ *     returns BUZZ_ECAPACITY otherwise: no kernel is handed a row the
+ *     workspace does not have.
  *   - A handle must not be used from two threads at once.
  *   - q, k, v share `kv_dtype`; attention output and scores are fp32.
  */

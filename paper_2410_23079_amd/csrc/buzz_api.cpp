@@ -325,6 +325,26 @@ bool evict_sizes(const buzz_cache_t* c, int64_t n, int64_t n_old, EvictSizes* z)
     return true;
 }
 
+// Whether an eviction with these sizes stays inside what the workspace layout set aside: the old region
+// (which ends where the ring begins), the list of selected rows, the staging rows.  The old-region bound is
+// the caller-visible capacity; the others hold by construction of the layout and are checked all the same,
+// before anything is enqueued: a launch must never be given a row the workspace does not have.
+bool evict_uses_one_launch(const buzz_cache_t* c, int64_t n_old, const EvictSizes& z)
+{
+    return !(c->cfg.flags & BUZZ_FLAG_GLOBAL_TOPK) && z.old2 == n_old &&
+           ((int64_t)c->cfg.segment + c->L.keep) * (int64_t)(4 * sizeof(float)) <= 65536;
+}
+bool evict_fits(const buzz_cache_t* c, int64_t n_old, const EvictSizes& z)
+{
+    const Layout& L = c->L;
+    if (z.old2 + z.new2 > L.old_cap) return false;
+    if (c->cfg.sink + z.old2 + z.new2 > L.ring_base) return false;
+    if (c->cfg.flags & BUZZ_FLAG_GLOBAL_TOPK) return z.new2 <= L.st_rows && z.new2 <= L.sel_stride;
+    if (evict_uses_one_launch(c, n_old, z)) return true;
+    if (z.old2 < n_old && z.old2 > L.st_rows) return false;
+    return z.new2 <= L.sel_stride;
+}
+
 // Applies the score update the last decode step left pending, so that the scores are current.
 int flush_scores(buzz_cache_t* c, hipStream_t st)
 {
@@ -347,11 +367,11 @@ int evict_impl(buzz_cache_t* c, hipStream_t st)
 {
     const buzz_config_t& cfg = c->cfg;
     const Layout& L = c->L;
-    const int64_t k = cfg.sink, s = cfg.segment, keep = L.keep;
+    const int64_t k = cfg.sink;
     EvictSizes z;
     if (!evict_sizes(c, c->n(), c->n_old, &z)) return BUZZ_OK; // Remark 1
     const int64_t newc = z.newc, sh = L.old_stride, old2 = z.old2, new2 = z.new2;
-    if (old2 + new2 > L.old_cap) return BUZZ_ECAPACITY;
+    if (!evict_fits(c, c->n_old, z)) return BUZZ_ECAPACITY;
     if (cfg.flags & BUZZ_FLAG_GLOBAL_TOPK) {
         // H2O-style: the top `keep` of ALL rows between sink and window survive.  Survivors may sit anywhere in
         // the old region or the ring and land where old rows are, so they travel through the staging rows.
@@ -387,7 +407,7 @@ int evict_impl(buzz_cache_t* c, hipStream_t st)
     }
     // Old rows that stay where they are (old stride 1) leave only the new rows to deal with, and one launch
     // does that: a score update still pending stays pending for every row that keeps its place.
-    const bool in_place = old2 == c->n_old && (s + keep) * (int64_t)(4 * sizeof(float)) <= 65536;
+    const bool in_place = evict_uses_one_launch(c, c->n_old, z);
     if (in_place) {
         if (!c->dry && new2 > 0) {
             if (c->prof) c->prof_evictions += 1;
@@ -539,13 +559,13 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
     const int64_t k = cfg.sink, w = cfg.window, s = cfg.segment, keep = L.keep, T = cfg.evict_every;
     const int64_t M = N - k - w;                                // prompt tokens between sink and window
     const bool sample = M >= T;
-    int64_t survivors = 0, sel_step = 1;
+    int64_t survivors = 0, selected = 0, sel_step = 1;
     const bool global = cfg.flags & BUZZ_FLAG_GLOBAL_TOPK;
     if (sample && global) {
-        survivors = keep < M ? keep : M;                        // H2O-style: one segment over the whole middle
+        survivors = selected = keep < M ? keep : M;             // H2O-style: one segment over the whole middle
     } else if (sample) {
         const int64_t last = M % s < keep ? M % s : keep;
-        survivors = keep * (M / s) + last;
+        survivors = selected = keep * (M / s) + last;           // rows the selection lists; Remark 2 may thin them
         if (L.old_stride > 1 && (cfg.capacity > 0 || (cfg.flags & BUZZ_FLAG_THRESHOLD_TOTAL))) {   // Remark 2: sample until it fits
             while (survivors > L.old_cap) {
                 const int64_t nxt = ceil_div(survivors, L.old_stride);
@@ -559,6 +579,8 @@ int buzz_prefill(buzz_cache_t* c, const void* kp, const void* vp, int64_t N, con
     const int64_t sink_rows = N < k ? N : k;
     const int64_t tail_rows = sample ? w : N - sink_rows;
     if (tail_rows > L.ring_cap) return BUZZ_ECAPACITY;
+    // the layout's own regions: selected rows fit the selection list, survivors end before the ring begins
+    if (selected > L.sel_stride || sink_rows + survivors > L.ring_base) return BUZZ_ECAPACITY;
 
     if (!c->dry) {
         float* ps = c->at<float>(L.pscore);
@@ -666,9 +688,35 @@ int decode_step_impl(buzz_cache_t* c, const void* q, const void* k_new, const vo
         if (evict_sizes(c, n, c->n_old, &z)) {
             const int64_t count = (cfg.flags & BUZZ_FLAG_THRESHOLD_TOTAL) ? c->n_old + z.newc : z.newc;
             evict_after = count >= cfg.evict_every;
-            if (evict_after && z.old2 + z.new2 > L.old_cap) return BUZZ_ECAPACITY;
+            if (evict_after && !evict_fits(c, c->n_old, z)) return BUZZ_ECAPACITY;
         }
     }
+
+    // the row being written must lie inside the sink or the ring, the rows stored linearly before the ring
+    if (to_sink ? (new_phys < 0 || new_phys >= cfg.sink)
+                : (new_phys < L.ring_base || new_phys >= (int64_t)L.ring_base + L.ring_cap || new_phys >= L.cap))
+        return BUZZ_ECAPACITY;
+    if (sink_filled + c->n_old > L.ring_base) return BUZZ_ECAPACITY;
+    // Key-range splits.  Few, long blocks amortise the per-block merge, and a block count that fills every
+    // compute unit the same number of times avoids a tail.  Automatic choice: one block per compute unit, 8
+    // waves wide (floor(CUs / units) splits); with at least one unit per CU a unit is a single block and nothing
+    // is merged across blocks at all.
+    const int cus = compute_units();
+    const int tile = attn_tile_rows(cfg.kv_dtype, cfg.head_dim, L.G);
+    int64_t S = c->user_splits > 0 ? c->user_splits : (L.units >= cus ? 1 : cus / L.units);
+    // a split of fewer than kMinSplitRows rows costs more in merge latency than it saves in streaming
+    if (c->user_splits == 0 && S > ceil_div(n, kMinSplitRows)) S = ceil_div(n, kMinSplitRows);
+    if (S < 1) S = 1;
+    if (S > L.s_cap) S = L.s_cap;
+    int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
+    const int stage_cap = stage_floats(L.G, cfg.head_dim);
+    while ((rps + 4) * L.G > stage_cap) {                      // LDS staging bound (+ alignment slack)
+        S += 1;
+        rps = ceil_div(ceil_div(n, S), tile) * tile;
+    }
+    const int64_t n_splits = ceil_div(n, rps);
+    // the workspace holds s_cap partial results per unit (the static scratch has its own bound below)
+    if (!static_scratch && n_splits > L.s_cap) return BUZZ_ECAPACITY;
 
     if (!c->dry) {
         AttnArgs a{};
@@ -695,25 +743,8 @@ int decode_step_impl(buzz_cache_t* c, const void* q, const void* k_new, const vo
         a.streaming = (cfg.flags & BUZZ_FLAG_STREAMING) ? 1
                       : (cfg.flags & BUZZ_FLAG_CACHED) ? 0 : (step_bytes > kLastLevelCacheBytes);
         a.fixed_tiles = (cfg.flags & BUZZ_FLAG_DETERMINISTIC) ? 1 : 0;
-        const int tile = attn_tile_rows(cfg.kv_dtype, cfg.head_dim, L.G);
-        // Few, long blocks amortise the per-block merge, and a block count that fills every compute unit the
-        // same number of times avoids a tail.  Automatic choice: one block per compute unit, 8 waves wide
-        // (floor(CUs / units) splits); with at least one unit per CU a unit is a single block and nothing is
-        // merged across blocks at all.
-        const int cus = compute_units();
-        int64_t S = c->user_splits > 0 ? c->user_splits : (L.units >= cus ? 1 : cus / L.units);
-        // a split of fewer than kMinSplitRows rows costs more in merge latency than it saves in streaming
-        if (c->user_splits == 0 && S > ceil_div(n, kMinSplitRows)) S = ceil_div(n, kMinSplitRows);
-        if (S < 1) S = 1;
-        if (S > L.s_cap) S = L.s_cap;
-        int64_t rps = ceil_div(ceil_div(n, S), tile) * tile;
-        const int stage_cap = stage_floats(L.G, cfg.head_dim);
-        while ((rps + 4) * L.G > stage_cap) {                  // LDS staging bound (+ alignment slack); s_cap covers it
-            S += 1;
-            rps = ceil_div(ceil_div(n, S), tile) * tile;
-        }
         a.rows_per_split = (int32_t)rps;
-        a.n_splits = (int32_t)ceil_div(n, rps);
+        a.n_splits = (int32_t)n_splits;
         if (static_scratch && a.n_splits > 1) {
             // partials are laid out [units][n_splits] in the static array; the counters are cleared by a small
             // kernel (not a memset: the caller may be capturing a graph), whatever the last call left there
@@ -799,7 +830,7 @@ int buzz_cache_import(buzz_cache_t* c, const void* k, const void* v, const float
     const int64_t sink_rows = n - n_old < cfg.sink ? n - n_old : cfg.sink;
     if (n_old > 0 && sink_rows < cfg.sink) return BUZZ_EINVAL;
     const int64_t tail_rows = n - sink_rows - n_old;
-    if (tail_rows > L.ring_cap) return BUZZ_ECAPACITY;
+    if (tail_rows > L.ring_cap || sink_rows + n_old > L.ring_base) return BUZZ_ECAPACITY;
     if (!c->dry) {
         hipStream_t st = (hipStream_t)hip_stream;
         if (int rc = probe_die_placement(st)) return rc;

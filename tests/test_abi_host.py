@@ -101,6 +101,39 @@ def test_workspace_grows_with_context_and_covers_kv():
     assert big > kv_min
 
 
+@pytest.mark.parametrize("dtype,elem", [("fp32", 4), ("fp16", 2), ("bf16", 2)])
+def test_workspace_size_follows_the_rows_the_cache_must_hold(dtype, elem):
+    """The workspace holds K and V for every row the cache can ever retain (found by driving a dry-run cache
+    to max_context), and not a multiple of that."""
+    B, H, D, w, T, ctx = 2, 4, 128, 4096, 64, 12288
+    c = cfg(batch=B, n_q_heads=H, n_kv_heads=H, head_dim=D, kv_dtype=dtype, window=w, evict_every=T, segment=64,
+            keep=8, old_stride=1, max_context=ctx)
+    g = BuzzCache(c)
+    g.prefill(None, None, n_prompt=8192)
+    rows = g.lengths()[0]
+    for _ in range(ctx - 8192):
+        g.decode_step(None, None, None, None)
+        rows = max(rows, g.lengths()[0])
+    per_row = 2 * D * elem + 8                               # K, V, score, position
+    need = B * H * rows * per_row
+    got = workspace_bytes(c)
+    assert got >= need
+    # side arrays (logit buffers, prompt scores, selection lists, statistics) are small next to K and V here
+    assert got <= 1.3 * need + B * H * ctx * 4 + (8 << 20)
+
+
+def test_a_long_cache_with_wide_groups_has_room_for_its_splits():
+    """Eight query heads per kv head and 16k rows need 16 key-range splits per unit for the LDS staging of the
+    logits; the workspace must have partial-result slots for them although 512 units alone would get 8."""
+    c = cfg(batch=32, n_q_heads=128, n_kv_heads=16, head_dim=64, kv_dtype="bf16", sink=4, window=16000, segment=64,
+            keep=8, evict_every=64, old_stride=1, max_context=16400)
+    g = BuzzCache(c)
+    g.prefill(None, None, n_prompt=16100)
+    for _ in range(200):
+        g.decode_step(None, None, None, None)               # would say BUZZ_ECAPACITY if the splits did not fit
+    assert g.lengths()[0] >= 16004
+
+
 def closed_form(N, steps, k, w, s, c, T, sh):
     def evict(n, n_old):
         if n <= k + w:
@@ -183,6 +216,46 @@ def test_explicit_capacity_and_remark2_resampling():
     with pytest.raises(BuzzError) as e:
         g2.prefill(None, None, n_prompt=512)
     assert e.value.code == -2
+
+
+def test_boundaries_of_the_prefill_bookkeeping():
+    """Literal sizes at the edges: exactly T tokens between sink and window (Alg. 1: the eviction fires when the
+    count reaches T), survivors that exactly fill the capacity (Remark 2 samples again only while they do not
+    fit), a prompt that exactly fills the sink, and a prompt of exactly max_context tokens."""
+    k, w, s, T = 4, 10, 5, 20
+    for between, want in ((T - 1, (k + w + T - 1, 0)), (T, (k + 4 + w, 4)), (T + 1, (k + 5 + w, 5))):
+        g = BuzzCache(cfg(sink=k, window=w, segment=s, keep=1, evict_every=T, old_stride=1, max_context=200))
+        g.prefill(None, None, n_prompt=k + w + between)
+        assert g.lengths()[:2] == want, between
+    # 100 tokens between sink and window, one survivor per 5 = 20 survivors
+    for room, want_old in ((20, 20), (19, 10), (10, 10), (9, 5)):     # s^ = 2: 20 -> 10 -> 5
+        g = BuzzCache(cfg(sink=k, window=w, segment=s, keep=1, evict_every=T, old_stride=2,
+                          capacity=k + w + T + room, max_context=400))
+        g.prefill(None, None, n_prompt=k + w + 100)
+        assert g.lengths()[1] == want_old, room
+    # every token survives (keep >= segment): the survivors are all 100 tokens and must be accepted
+    g = BuzzCache(cfg(sink=k, window=w, segment=s, keep=s, evict_every=T, old_stride=1, max_context=k + w + 100))
+    g.prefill(None, None, n_prompt=k + w + 100)
+    assert g.lengths()[:2] == (k + w + 100, 100)
+    with pytest.raises(BuzzError) as e:                        # ... and the context is full
+        g.decode_step(None, None, None, None)
+    assert e.value.code == -2
+    # a prompt that exactly fills the sink: the next token goes to the ring, not to a fifth sink row
+    g = BuzzCache(cfg(sink=k, window=w, segment=s, keep=1, evict_every=T, old_stride=1, max_context=200))
+    g.prefill(None, None, n_prompt=k)
+    for i in range(w + T + 3):
+        g.decode_step(None, None, None, None)
+    assert g.lengths()[0] == k + 4 + w + 3                     # one eviction of T = 20 tokens left 4
+
+
+def test_the_entry_point_without_allocation_keeps_the_same_books():
+    a, b = BuzzCache(cfg(flags=DRY | FLAG_AUTO_EVICT)), BuzzCache(cfg(flags=DRY | FLAG_AUTO_EVICT))
+    a.prefill(None, None, n_prompt=300)
+    b.prefill(None, None, n_prompt=300)
+    for _ in range(100):
+        a.decode_step(None, None, None, None)
+        b.decode_step_static(None, None, None, None)
+        assert a.lengths() == b.lengths()
 
 
 def test_theorem_threshold_helper():
