@@ -358,3 +358,21 @@ def test_import_restores_the_bookkeeping():
     assert lib.buzz_cache_import(h, None, None, None, None, 6, 3, 6, None) == -1         # old rows without a full sink
     assert lib.buzz_cache_import(h, None, None, None, None, 10, 0, 5000, None) == -2     # beyond max_context
     assert lib.buzz_cache_import(h, None, None, None, None, 2500, 0, 2500, None) == -2   # more buffered rows than the ring holds
+    # the edges themselves are inside: as many tokens as max_context, a ring exactly full (window 64 + T 16 rows)
+    assert lib.buzz_cache_import(h, None, None, None, None, 10, 0, 3000, None) == 0
+    assert lib.buzz_cache_import(h, None, None, None, None, 4 + 80, 0, 100, None) == 0
+    assert b.lengths() == (84, 0, 16)
+    assert lib.buzz_cache_import(h, None, None, None, None, 4 + 81, 0, 100, None) == -2
+    assert b.lengths() == (84, 0, 16)                                                    # the failed call changed nothing
+
+
+def test_a_prompt_shorter_than_the_sink_fills_the_sink_first():
+    """Remark 1: the first tokens go to the sink; the counts grow by one per token either way."""
+    g = BuzzCache(cfg(sink=4, window=10, segment=5, keep=1, evict_every=20, old_stride=1, max_context=100))
+    g.prefill(None, None, n_prompt=2)
+    seen = []
+    for _ in range(40):
+        g.decode_step(None, None, None, None)
+        seen.append(g.lengths())
+    assert seen[0] == (3, 0, 0) and seen[1] == (4, 0, 0) and seen[11] == (14, 0, 0) and seen[12] == (15, 0, 1)
+    assert seen[31] == (4 + 4 + 10, 4, 0)                   # 34 tokens: 20 between sink and window -> 4 survivors
