@@ -222,7 +222,7 @@ def test_prefill_scores_when_logits_jump(G):
     print(f"[parity]   jumping logits G{G}: prefill-score {st['prefill_score']:.2e} out {st['out']:.2e}", flush=True)
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_configurations(seed):
     """Seeded random shapes, cache parameters and variants through the whole lock-step protocol."""
     r = np.random.default_rng(9000 + seed)
@@ -250,6 +250,55 @@ def test_random_configurations(seed):
     wl = small(batch=B, n_kv_heads=Hkv, n_q_heads=Hkv * G, head_dim=D, dtype=dtype, prompt=N, decode_steps=steps,
                sink=k, window=w, segment=s, keep=c, evict_every=T, old_stride=old_stride, n_obs=min(N, int(r.integers(0, 40))))
     run(wl, deterministic=bool(seed % 2), device_merge=bool((seed // 2) % 2), **kw)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_long_configurations(seed):
+    """The same with long prompts, windows and segments and large keep (several blocks per unit, long segments)."""
+    r = np.random.default_rng(770000 + seed)
+    dtype = ["fp32", "fp16", "bf16"][seed % 3]
+    D = int(r.choice([64, 128, 128, 256]))
+    G = int(r.choice([1, 1, 2, 4, 5, 8]))
+    Hkv = int(r.choice([1, 2, 4, 8]))
+    B = int(r.choice([1, 2, 4]))
+    k, w = int(r.integers(0, 9)), int(r.integers(0, 5000))
+    s = int(r.integers(1, 300))
+    c = int(r.integers(0, 40))
+    T = int(r.integers(1, 300))
+    old_stride = int(r.choice([1, 1, 1, 0, 2, 5]))
+    N = int(r.integers(0, 24000))
+    steps = int(min(400, r.integers(T + 1, 2 * T + 40)))
+    variant = seed % 5
+    kw = {}
+    if variant == 1:
+        kw["log_n"] = True
+    elif variant == 2 and c > 0:
+        kw["global_topk"] = True
+        c = int(r.integers(1, 600))
+    elif variant == 3:
+        kw["interval_new"] = True
+    wl = small(batch=B, n_kv_heads=Hkv, n_q_heads=Hkv * G, head_dim=D, dtype=dtype, prompt=N, decode_steps=steps,
+               sink=k, window=w, segment=s, keep=c, evict_every=T, old_stride=old_stride, n_obs=min(N, int(r.integers(0, 48))))
+    run(wl, deterministic=bool(seed % 2), device_merge=bool((seed // 2) % 2), **kw)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_prompt_scoring(seed):
+    """Prompt scores from all or a random number of prompt queries, both scoring paths, random shapes."""
+    r = np.random.default_rng(880000 + seed)
+    dtype = ["fp16", "bf16", "fp16", "bf16", "fp32"][seed % 5]
+    D = int(r.choice([64, 128, 128, 256]))
+    G = int(r.choice([1, 2, 4, 8]))
+    Hkv = int(r.choice([1, 2, 3]))
+    B = int(r.choice([1, 2]))
+    N = int(r.integers(1, 1200 if dtype == "fp32" else 5200))
+    n_obs = N if seed % 2 == 0 else int(r.integers(0, N + 1))
+    k, w = int(r.integers(0, 6)), int(r.integers(0, 600))
+    s, c, T = int(r.integers(1, 80)), int(r.integers(0, 6)), int(r.integers(1, 100))
+    kw = {"log_n": True} if seed % 3 == 0 else {}
+    wl = small(batch=B, n_kv_heads=Hkv, n_q_heads=Hkv * G, head_dim=D, dtype=dtype, prompt=N, decode_steps=3,
+               sink=k, window=w, segment=s, keep=c, evict_every=T, old_stride=1, n_obs=n_obs)
+    run(wl, **kw)
 
 
 # ------------------------------------------------------------------ degenerate cases of the method
