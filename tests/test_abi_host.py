@@ -248,6 +248,26 @@ def test_boundaries_of_the_prefill_bookkeeping():
     assert g.lengths()[0] == k + 4 + w + 3                     # one eviction of T = 20 tokens left 4
 
 
+def test_explicit_capacity_at_its_smallest():
+    """`capacity` counts sink, old rows, window and the T buffered rows: with no room for old rows it is still a
+    valid cache (nothing survives an eviction), one row less is not; the H2O-style variant needs room for its
+    `keep` survivors."""
+    from paper_2410_23079_amd import FLAG_GLOBAL_TOPK
+    k, w, T = 4, 10, 20
+    g = BuzzCache(cfg(sink=k, window=w, segment=5, keep=0, evict_every=T, old_stride=1, capacity=k + w + T, max_context=300))
+    g.prefill(None, None, n_prompt=100)
+    assert g.lengths()[:2] == (k + w, 0)
+    with pytest.raises(BuzzError) as e:
+        BuzzCache(cfg(sink=k, window=w, segment=5, keep=0, evict_every=T, old_stride=1, capacity=k + w + T - 1, max_context=300))
+    assert e.value.code == -1
+    BuzzCache(cfg(sink=k, window=w, segment=5, keep=7, evict_every=T, capacity=k + 7 + w + T, max_context=300,
+                  flags=DRY | FLAG_GLOBAL_TOPK))
+    with pytest.raises(BuzzError) as e:
+        BuzzCache(cfg(sink=k, window=w, segment=5, keep=7, evict_every=T, capacity=k + 7 + w + T - 1, max_context=300,
+                      flags=DRY | FLAG_GLOBAL_TOPK))
+    assert e.value.code == -1
+
+
 def test_the_entry_point_without_allocation_keeps_the_same_books():
     a, b = BuzzCache(cfg(flags=DRY | FLAG_AUTO_EVICT)), BuzzCache(cfg(flags=DRY | FLAG_AUTO_EVICT))
     a.prefill(None, None, n_prompt=300)
